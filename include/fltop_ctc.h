@@ -1,0 +1,143 @@
+/*
+ * fltop_ctc.h -- C ABI of the FLToP CTC decoder for AMD MI355X (gfx950).
+ *
+ * What is computed (paper: "FLToP CTC", Sec. 3, Algorithm 1): CTC prefix beam
+ * search in which, at every frame, only the tokens whose probability is at
+ * least R times the frame's top probability are expanded.  Per utterance:
+ *
+ *   beam <- { (empty prefix, score 0) }
+ *   for each frame t < length:
+ *       S_t  <- { v : lp[t][v] >= max_v lp[t][v] + ln R }      (relative threshold)
+ *       expand every beam entry by every token of S_t           (blank / repeat / extend)
+ *       merge equal prefixes (log-sum-exp), keep the best `beam` (SelectTopK)
+ *   return the best prefix                                      (GetHighestScorePrefix)
+ *
+ * Algorithm 1 leaves the CTC collapse abstract ("prefix + token", "score +
+ * logit"); this library uses the standard two-mass form: a prefix carries
+ * p_b (log-mass of its alignments ending in blank) and p_nb (ending in its last
+ * token); blank feeds p_b of the same prefix, a repeat of the last token feeds
+ * p_nb of the same prefix and -- from p_b only -- the prefix extended by that
+ * token, any other token extends from p_b (+) p_nb.  A prefix's score is
+ * LSE(p_b, p_nb).  The optional LM term of Algorithm 1 (score' += LM(prefix'))
+ * is a dense bigram table applied once per emitted token.
+ *
+ * All decoding arithmetic on scores is fp64; the threshold test is one fp32
+ * addition and fp32 comparisons.  Score ties are ordered by a 64-bit prefix
+ * hash: h(empty) = 0x9E3779B97F4A7C15, h(p + c) = mix(h(p) + 0x9E3779B97F4A7C15
+ * * (c + 1)), mix = the splitmix64 output function; smaller hash wins.  Equal
+ * prefixes are recognised by this hash.
+ *
+ * Conventions: "dev" = device (HBM) pointer, "host" = host pointer.  Arrays are
+ * row-major and densely packed.  The caller owns every buffer; the library
+ * allocates nothing, keeps no state between calls and may be called
+ * concurrently on different streams with different workspaces.  All work is
+ * enqueued on `stream`; no entry point synchronises with the host, so outputs
+ * are valid once the stream has reached that point.  Every function that
+ * returns int returns FLTOP_OK (0) or a negative FLTOP_ERR_* value; on an
+ * error nothing has been enqueued.  There is no CPU fallback.
+ */
+#ifndef FLTOP_CTC_H_
+#define FLTOP_CTC_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define FLTOP_OK                  0
+#define FLTOP_ERR_NULL_POINTER   -1  /* a required pointer is NULL                          */
+#define FLTOP_ERR_BAD_SHAPE      -2  /* B < 1, T < 1 or V < 2                               */
+#define FLTOP_ERR_BAD_BEAM       -3  /* beam < 1 or beam > FLTOP_MAX_BEAM                   */
+#define FLTOP_ERR_BAD_THRESHOLD  -4  /* rel_threshold outside [0, 1] or NaN                 */
+#define FLTOP_ERR_WORKSPACE      -5  /* workspace smaller than fltop_ctc_workspace_bytes()  */
+#define FLTOP_ERR_VOCAB_TOO_BIG  -6  /* V > FLTOP_MAX_VOCAB                                 */
+#define FLTOP_ERR_HIP            -7  /* a HIP call or kernel launch failed                  */
+#define FLTOP_ERR_ALIGNMENT      -8  /* workspace not 256-byte aligned                      */
+
+#define FLTOP_MAX_BEAM   128
+#define FLTOP_MAX_VOCAB  4096
+
+/* Decoder settings (host POD, read during the call only).
+ * Algorithm 1's arguments: beam_size -> beam, R -> rel_threshold, LM -> the
+ * three lm fields.  Its N (static top-N stage) is V here and its
+ * beam_threshold is not applied. */
+typedef struct fltop_params {
+    int32_t      beam;             /* 1 .. FLTOP_MAX_BEAM                                       */
+    float        rel_threshold;    /* R in [0,1]; 0 keeps every token (unpruned search)         */
+    const float* lm_table;         /* dev [V,V] fp32 log-probs, row = previous token (row 0 for
+                                      the first token of a prefix), or NULL for no LM           */
+    float        lm_weight;        /* extension adds lm_weight * lm_table[prev][tok]            */
+    float        insertion_bonus;  /*                + insertion_bonus   (only if lm_table)     */
+    /* Optional export of the whole final beam in rank order (all NULL to skip).               */
+    int32_t*     nbest_count;      /* dev [B]          entries written for utterance b          */
+    int32_t*     nbest_tokens;     /* dev [B,beam,T]   entry e of b: first nbest_lengths tokens */
+    int32_t*     nbest_lengths;    /* dev [B,beam]                                              */
+    double*      nbest_pb;         /* dev [B,beam]     log-mass ending in blank                 */
+    double*      nbest_pnb;        /* dev [B,beam]     log-mass ending in the last token        */
+} fltop_params;
+
+/* Counters accumulated (added to) by fltop_ctc_decode; zero them beforehand. */
+typedef struct fltop_stats {
+    uint64_t frames;            /* valid frames decoded                                        */
+    uint64_t sum_survivors;     /* sum over frames of |S_t|                                    */
+    uint64_t sum_candidates;    /* sum over frames of distinct live candidate prefixes         */
+    uint64_t peak_candidates;   /* max over frames (and utterances) of the same                */
+    uint64_t sum_beam;          /* sum over frames of entries kept by the top-`beam` cut       */
+    uint64_t select_passes;     /* histogram passes spent in the top-`beam` selection          */
+    uint64_t exact_rankings;    /* selections that needed the exact (score, hash) ranking      */
+    uint64_t overflow_drops;    /* entries dropped because a hash collision overfilled a beam  */
+} fltop_stats;
+
+/* Bytes of device workspace fltop_ctc_decode / fltop_ctc_prune need for these
+ * shapes (0 if the shapes are invalid).  Holds the per-frame survivor lists
+ * and the prefix trie. */
+size_t fltop_ctc_workspace_bytes(int32_t B, int32_t T, int32_t V, int32_t beam);
+
+/* The whole path: survivor lists for all valid frames, then the beam search,
+ * then the best prefix of every utterance.
+ *   logprobs     dev [B,T,V] fp32 log-probabilities, token 0 = blank.  -inf is
+ *                allowed; NaN is undefined.  Rows need not be normalised.
+ *   lengths      dev [B] int32; values are clamped to [0,T]; frames at or
+ *                beyond lengths[b] are never read.
+ *   workspace    dev, 256-byte aligned, >= fltop_ctc_workspace_bytes(B,T,V,beam).
+ *   out_tokens   dev [B,T] int32; row b holds out_lengths[b] tokens (rest untouched).
+ *   out_lengths  dev [B] int32.
+ *   out_scores   dev [B] fp32: LSE(p_b,p_nb) of the returned prefix, rounded
+ *                from fp64.  A zero-length utterance returns the empty prefix
+ *                with score 0; an utterance whose every route has zero mass
+ *                returns the empty prefix with score -inf.
+ *   stats        dev or NULL.
+ */
+int fltop_ctc_decode(const float* logprobs, const int32_t* lengths,
+                     int32_t B, int32_t T, int32_t V, const fltop_params* params,
+                     void* workspace, size_t workspace_bytes,
+                     int32_t* out_tokens, int32_t* out_lengths, float* out_scores,
+                     fltop_stats* stats, void* hip_stream);
+
+/* The first stage alone (Algorithm 1's top-emission lookup and relative-
+ * threshold test, which do not depend on the hypotheses, for every valid frame
+ * at once): writes the survivor lists into `workspace` in the library's
+ * internal layout.  Same argument rules as fltop_ctc_decode (`beam` only sizes
+ * the workspace check). */
+int fltop_ctc_prune(const float* logprobs, const int32_t* lengths,
+                    int32_t B, int32_t T, int32_t V, int32_t beam, float rel_threshold,
+                    void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Copy the survivor lists fltop_ctc_prune left in `workspace` into plain
+ * arrays: counts dev [B*T] int32 (0 for frames beyond the length), tokens dev
+ * [B*T,V] int32 and values dev [B*T,V] fp32 (first counts[f] entries of row f,
+ * ascending token id, rest untouched), frame_max dev [B*T] fp32 (NULL to skip). */
+int fltop_ctc_unpack_survivors(const void* workspace, size_t workspace_bytes,
+                               int32_t B, int32_t T, int32_t V, int32_t beam,
+                               int32_t* counts, int32_t* tokens, float* values,
+                               float* frame_max, void* hip_stream);
+
+/* Human-readable name of a status code (static storage). */
+const char* fltop_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FLTOP_CTC_H_ */

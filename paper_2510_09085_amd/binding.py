@@ -1,0 +1,205 @@
+"""Thin ctypes binding of the C ABI in include/fltop_ctc.h (argument marshalling only).
+
+Every step of the decode runs in the HIP library; torch is used for device
+memory and the current stream.  There is no fallback: if the shared library is
+missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libfltop_ctc.so")
+
+MAX_BEAM = 128
+MAX_VOCAB = 4096
+
+EXPORTS = ("fltop_ctc_workspace_bytes", "fltop_ctc_decode", "fltop_ctc_prune",
+           "fltop_ctc_unpack_survivors", "fltop_status_string")
+
+
+class FltopParams(ctypes.Structure):
+    _fields_ = [
+        ("beam", ctypes.c_int32),
+        ("rel_threshold", ctypes.c_float),
+        ("lm_table", ctypes.c_void_p),
+        ("lm_weight", ctypes.c_float),
+        ("insertion_bonus", ctypes.c_float),
+        ("nbest_count", ctypes.c_void_p),
+        ("nbest_tokens", ctypes.c_void_p),
+        ("nbest_lengths", ctypes.c_void_p),
+        ("nbest_pb", ctypes.c_void_p),
+        ("nbest_pnb", ctypes.c_void_p),
+    ]
+
+
+STATS_FIELDS = ("frames", "sum_survivors", "sum_candidates", "peak_candidates", "sum_beam",
+                "select_passes", "exact_rankings", "overflow_drops")
+
+_lib = None
+
+
+class FltopError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+def load():
+    """Load the HIP library built in-tree; raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2510_09085_amd.build`")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32, f32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_float, ctypes.c_size_t
+    lib.fltop_ctc_workspace_bytes.restype = sz
+    lib.fltop_ctc_workspace_bytes.argtypes = [i32, i32, i32, i32]
+    lib.fltop_ctc_decode.restype = ctypes.c_int
+    lib.fltop_ctc_decode.argtypes = [vp, vp, i32, i32, i32, ctypes.POINTER(FltopParams), vp, sz,
+                                     vp, vp, vp, vp, vp]
+    lib.fltop_ctc_prune.restype = ctypes.c_int
+    lib.fltop_ctc_prune.argtypes = [vp, vp, i32, i32, i32, i32, f32, vp, sz, vp]
+    lib.fltop_ctc_unpack_survivors.restype = ctypes.c_int
+    lib.fltop_ctc_unpack_survivors.argtypes = [vp, sz, i32, i32, i32, i32, vp, vp, vp, vp, vp]
+    lib.fltop_status_string.restype = ctypes.c_char_p
+    lib.fltop_status_string.argtypes = [ctypes.c_int]
+    _lib = lib
+    return lib
+
+
+def status_string(status: int) -> str:
+    return load().fltop_status_string(int(status)).decode()
+
+
+def workspace_bytes(B: int, T: int, V: int, beam: int) -> int:
+    return int(load().fltop_ctc_workspace_bytes(B, T, V, beam))
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream_handle(stream) -> ctypes.c_void_p:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _check_inputs(logprobs: torch.Tensor, lengths: torch.Tensor):
+    if not (logprobs.is_cuda and lengths.is_cuda):
+        raise ValueError("logprobs and lengths must be device tensors")
+    if logprobs.dtype != torch.float32 or lengths.dtype != torch.int32:
+        raise ValueError("logprobs must be float32 and lengths int32")
+    if logprobs.dim() != 3 or not logprobs.is_contiguous() or not lengths.is_contiguous():
+        raise ValueError("logprobs must be a contiguous [B,T,V] tensor")
+    if lengths.numel() != logprobs.shape[0]:
+        raise ValueError("lengths must have B entries")
+
+
+def alloc_workspace(B: int, T: int, V: int, beam: int, device) -> torch.Tensor:
+    n = workspace_bytes(B, T, V, beam)
+    if n == 0:
+        raise FltopError(-2, "fltop_ctc_workspace_bytes")
+    return torch.empty(n, dtype=torch.uint8, device=device)
+
+
+def decode_raw(logprobs, lengths, params: FltopParams, workspace, workspace_nbytes, out_tokens,
+               out_lengths, out_scores, stats, stream=None) -> int:
+    """Direct call of fltop_ctc_decode; returns the status code (no checks, no allocation)."""
+    B, T, V = logprobs.shape
+    return int(load().fltop_ctc_decode(_ptr(logprobs), _ptr(lengths), B, T, V,
+                                       ctypes.byref(params), _ptr(workspace), workspace_nbytes,
+                                       _ptr(out_tokens), _ptr(out_lengths), _ptr(out_scores),
+                                       _ptr(stats), _stream_handle(stream)))
+
+
+def decode(logprobs: torch.Tensor, lengths: torch.Tensor, beam: int, rel_threshold: float, *,
+           lm_table: Optional[torch.Tensor] = None, lm_weight: float = 0.0,
+           insertion_bonus: float = 0.0, workspace: Optional[torch.Tensor] = None,
+           want_stats: bool = False, want_nbest: bool = False, stream=None) -> dict:
+    """fltop_ctc_decode on device tensors.  Returns device tensors (no host sync):
+    tokens [B,T] int32, lengths [B] int32, scores [B] fp32, and optionally stats
+    (uint64 [8], see STATS_FIELDS) and the n-best export."""
+    _check_inputs(logprobs, lengths)
+    B, T, V = logprobs.shape
+    dev = logprobs.device
+    if workspace is None:
+        workspace = alloc_workspace(B, T, V, beam, dev)
+    out = {
+        "tokens": torch.full((B, T), -1, dtype=torch.int32, device=dev),
+        "lengths": torch.zeros(B, dtype=torch.int32, device=dev),
+        "scores": torch.zeros(B, dtype=torch.float32, device=dev),
+    }
+    p = FltopParams()
+    p.beam = int(beam)
+    p.rel_threshold = float(rel_threshold)
+    p.lm_weight = float(lm_weight)
+    p.insertion_bonus = float(insertion_bonus)
+    if lm_table is not None:
+        if not (lm_table.is_cuda and lm_table.dtype == torch.float32 and lm_table.is_contiguous()
+                and tuple(lm_table.shape) == (V, V)):
+            raise ValueError("lm_table must be a contiguous float32 [V,V] device tensor")
+        p.lm_table = lm_table.data_ptr()
+    if want_nbest:
+        out["nbest_count"] = torch.zeros(B, dtype=torch.int32, device=dev)
+        out["nbest_tokens"] = torch.full((B, beam, T), -1, dtype=torch.int32, device=dev)
+        out["nbest_lengths"] = torch.zeros((B, beam), dtype=torch.int32, device=dev)
+        out["nbest_pb"] = torch.zeros((B, beam), dtype=torch.float64, device=dev)
+        out["nbest_pnb"] = torch.zeros((B, beam), dtype=torch.float64, device=dev)
+        p.nbest_count = out["nbest_count"].data_ptr()
+        p.nbest_tokens = out["nbest_tokens"].data_ptr()
+        p.nbest_lengths = out["nbest_lengths"].data_ptr()
+        p.nbest_pb = out["nbest_pb"].data_ptr()
+        p.nbest_pnb = out["nbest_pnb"].data_ptr()
+    stats = None
+    if want_stats:
+        stats = torch.zeros(len(STATS_FIELDS), dtype=torch.int64, device=dev)
+        out["stats"] = stats
+    rc = decode_raw(logprobs, lengths, p, workspace, workspace.numel(), out["tokens"],
+                    out["lengths"], out["scores"], stats, stream)
+    if rc != 0:
+        raise FltopError(rc, "fltop_ctc_decode")
+    out["workspace"] = workspace
+    return out
+
+
+def prune(logprobs: torch.Tensor, lengths: torch.Tensor, beam: int, rel_threshold: float, *,
+          workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """fltop_ctc_prune: survivor lists into the workspace (returned)."""
+    _check_inputs(logprobs, lengths)
+    B, T, V = logprobs.shape
+    if workspace is None:
+        workspace = alloc_workspace(B, T, V, beam, logprobs.device)
+    rc = int(load().fltop_ctc_prune(_ptr(logprobs), _ptr(lengths), B, T, V, int(beam),
+                                    float(rel_threshold), _ptr(workspace), workspace.numel(),
+                                    _stream_handle(stream)))
+    if rc != 0:
+        raise FltopError(rc, "fltop_ctc_prune")
+    return workspace
+
+
+def unpack_survivors(workspace: torch.Tensor, B: int, T: int, V: int, beam: int, stream=None):
+    """fltop_ctc_unpack_survivors -> (counts [B*T], tokens [B*T,V], values [B*T,V], frame_max [B*T])."""
+    dev = workspace.device
+    counts = torch.zeros(B * T, dtype=torch.int32, device=dev)
+    tokens = torch.full((B * T, V), -1, dtype=torch.int32, device=dev)
+    values = torch.zeros((B * T, V), dtype=torch.float32, device=dev)
+    fmax = torch.zeros(B * T, dtype=torch.float32, device=dev)
+    rc = int(load().fltop_ctc_unpack_survivors(_ptr(workspace), workspace.numel(), B, T, V,
+                                               int(beam), _ptr(counts), _ptr(tokens),
+                                               _ptr(values), _ptr(fmax), _stream_handle(stream)))
+    if rc != 0:
+        raise FltopError(rc, "fltop_ctc_unpack_survivors")
+    return counts, tokens, values, fmax
+
+
+def stats_dict(stats: torch.Tensor) -> dict:
+    vals = stats.cpu().tolist()
+    return dict(zip(STATS_FIELDS, vals))

@@ -1,0 +1,33 @@
+"""Compile the HIP decoder into an in-tree shared library for gfx950 (hipcc cross-compiles)."""
+from __future__ import annotations
+
+import glob
+import os
+import subprocess
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_ROOT = os.path.dirname(_PKG)
+LIB_PATH = os.path.join(_PKG, "libfltop_ctc.so")
+
+HIPCC_FLAGS = [
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    "-ffp-contract=off",  # keep fp64 score arithmetic as written (no fused multiply-add)
+    "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    "-Wall", "-Wno-unused-function",
+]
+
+
+def build(verbose: bool = False) -> str:
+    """Always recompiles; returns the path of the shared library."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    srcs = sorted(glob.glob(os.path.join(_PKG, "csrc", "*.hip")))
+    cmd = [hipcc, *HIPCC_FLAGS, "-I", os.path.join(_ROOT, "include"),
+           "-I", os.path.join(_PKG, "csrc"), *srcs, "-o", LIB_PATH]
+    if verbose:
+        print(" ".join(cmd))
+    subprocess.run(cmd, check=True)
+    return LIB_PATH
+
+
+if __name__ == "__main__":
+    print(build(verbose=True))

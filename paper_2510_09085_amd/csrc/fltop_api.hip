@@ -1,0 +1,120 @@
+// C ABI of the FLToP CTC decoder: argument checks, workspace carve-up, launches.
+// See include/fltop_ctc.h for the contract of every entry point.
+#include <cmath>
+
+#include "fltop_internal.h"
+
+namespace {
+
+int check_shapes(int32_t B, int32_t T, int32_t V, int32_t beam) {
+    if (B < 1 || T < 1 || V < 2) return FLTOP_ERR_BAD_SHAPE;
+    if (V > FLTOP_MAX_VOCAB) return FLTOP_ERR_VOCAB_TOO_BIG;
+    if (beam < 1 || beam > FLTOP_MAX_BEAM) return FLTOP_ERR_BAD_BEAM;
+    return FLTOP_OK;
+}
+
+int check_threshold(float r) {
+    if (!(r >= 0.0f && r <= 1.0f)) return FLTOP_ERR_BAD_THRESHOLD;  // NaN fails both
+    return FLTOP_OK;
+}
+
+int check_workspace(const void* ws, size_t bytes, size_t need) {
+    if (!ws) return FLTOP_ERR_NULL_POINTER;
+    if ((reinterpret_cast<uintptr_t>(ws) & 255u) != 0) return FLTOP_ERR_ALIGNMENT;
+    if (bytes < need) return FLTOP_ERR_WORKSPACE;
+    return FLTOP_OK;
+}
+
+// ln(R) rounded to fp32 once; R = 0 keeps everything.
+float ln_threshold(float r) {
+    if (r <= 0.0f) return -INFINITY;
+    return (float)std::log((double)r);
+}
+
+}  // namespace
+
+extern "C" size_t fltop_ctc_workspace_bytes(int32_t B, int32_t T, int32_t V, int32_t beam) {
+    if (check_shapes(B, T, V, beam) != FLTOP_OK) return 0;
+    return fltop::carve_workspace(nullptr, B, T, V, beam).bytes;
+}
+
+extern "C" int fltop_ctc_prune(const float* logprobs, const int32_t* lengths, int32_t B, int32_t T,
+                               int32_t V, int32_t beam, float rel_threshold, void* workspace,
+                               size_t workspace_bytes, void* hip_stream) {
+    if (!logprobs || !lengths) return FLTOP_ERR_NULL_POINTER;
+    int rc = check_shapes(B, T, V, beam);
+    if (rc != FLTOP_OK) return rc;
+    rc = check_threshold(rel_threshold);
+    if (rc != FLTOP_OK) return rc;
+    rc = check_workspace(workspace, workspace_bytes, fltop_ctc_workspace_bytes(B, T, V, beam));
+    if (rc != FLTOP_OK) return rc;
+    const fltop::Workspace ws = fltop::carve_workspace(workspace, B, T, V, beam);
+    hipError_t e = fltop::launch_prune(logprobs, lengths, B, T, V, ln_threshold(rel_threshold), ws,
+                                       static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? FLTOP_OK : FLTOP_ERR_HIP;
+}
+
+extern "C" int fltop_ctc_unpack_survivors(const void* workspace, size_t workspace_bytes, int32_t B,
+                                          int32_t T, int32_t V, int32_t beam, int32_t* counts,
+                                          int32_t* tokens, float* values, float* frame_max,
+                                          void* hip_stream) {
+    if (!counts || !tokens || !values) return FLTOP_ERR_NULL_POINTER;
+    int rc = check_shapes(B, T, V, beam);
+    if (rc != FLTOP_OK) return rc;
+    rc = check_workspace(workspace, workspace_bytes, fltop_ctc_workspace_bytes(B, T, V, beam));
+    if (rc != FLTOP_OK) return rc;
+    const fltop::Workspace ws =
+        fltop::carve_workspace(const_cast<void*>(workspace), B, T, V, beam);
+    hipError_t e = fltop::launch_unpack(ws, B, T, V, counts, tokens, values, frame_max,
+                                        static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? FLTOP_OK : FLTOP_ERR_HIP;
+}
+
+extern "C" int fltop_ctc_decode(const float* logprobs, const int32_t* lengths, int32_t B, int32_t T,
+                                int32_t V, const fltop_params* params, void* workspace,
+                                size_t workspace_bytes, int32_t* out_tokens, int32_t* out_lengths,
+                                float* out_scores, fltop_stats* stats, void* hip_stream) {
+    if (!logprobs || !lengths || !params || !out_tokens || !out_lengths || !out_scores)
+        return FLTOP_ERR_NULL_POINTER;
+    int rc = check_shapes(B, T, V, params->beam);
+    if (rc != FLTOP_OK) return rc;
+    rc = check_threshold(params->rel_threshold);
+    if (rc != FLTOP_OK) return rc;
+    const bool any_nbest = params->nbest_count || params->nbest_tokens || params->nbest_lengths ||
+                           params->nbest_pb || params->nbest_pnb;
+    const bool all_nbest = params->nbest_count && params->nbest_tokens && params->nbest_lengths &&
+                           params->nbest_pb && params->nbest_pnb;
+    if (any_nbest && !all_nbest) return FLTOP_ERR_NULL_POINTER;
+    rc = check_workspace(workspace, workspace_bytes,
+                         fltop_ctc_workspace_bytes(B, T, V, params->beam));
+    if (rc != FLTOP_OK) return rc;
+
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const fltop::Workspace ws = fltop::carve_workspace(workspace, B, T, V, params->beam);
+    hipError_t e = fltop::launch_prune(logprobs, lengths, B, T, V,
+                                       ln_threshold(params->rel_threshold), ws, stream);
+    if (e != hipSuccess) return FLTOP_ERR_HIP;
+    if (params->lm_table) {
+        e = fltop::launch_lm_bound(params->lm_table, V, params->lm_weight, params->insertion_bonus,
+                                   ws.lm_bound, stream);
+        if (e != hipSuccess) return FLTOP_ERR_HIP;
+    }
+    e = fltop::launch_beam(logprobs, lengths, B, T, V, *params, ws, out_tokens, out_lengths,
+                           out_scores, stats, stream);
+    return e == hipSuccess ? FLTOP_OK : FLTOP_ERR_HIP;
+}
+
+extern "C" const char* fltop_status_string(int status) {
+    switch (status) {
+        case FLTOP_OK: return "ok";
+        case FLTOP_ERR_NULL_POINTER: return "a required pointer is NULL";
+        case FLTOP_ERR_BAD_SHAPE: return "bad shape: need B >= 1, T >= 1, V >= 2";
+        case FLTOP_ERR_BAD_BEAM: return "beam outside 1..FLTOP_MAX_BEAM";
+        case FLTOP_ERR_BAD_THRESHOLD: return "rel_threshold outside [0,1]";
+        case FLTOP_ERR_WORKSPACE: return "workspace too small";
+        case FLTOP_ERR_VOCAB_TOO_BIG: return "V exceeds FLTOP_MAX_VOCAB";
+        case FLTOP_ERR_HIP: return "HIP launch failed";
+        case FLTOP_ERR_ALIGNMENT: return "workspace not 256-byte aligned";
+        default: return "unknown status";
+    }
+}

@@ -1,0 +1,84 @@
+// Internal definitions shared by the HIP translation units of the FLToP CTC decoder.
+#ifndef FLTOP_INTERNAL_H_
+#define FLTOP_INTERNAL_H_
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "fltop_ctc.h"
+
+namespace fltop {
+
+// One survivor of a frame: token id and its fp32 log-probability.
+struct alignas(8) Survivor {
+    int32_t tok;
+    float lp;
+};
+
+// Per-frame header written by the prune stage.
+struct alignas(16) FrameHdr {
+    int32_t count;   // |S_t| (0 for frames at or beyond the utterance length)
+    uint32_t offset; // first record, relative to the frame block's record region
+    float top;       // max_v lp[t][v]
+    int32_t pad;
+};
+
+// One node of the prefix trie (global memory): a prefix is a chain of nodes.
+struct alignas(8) TrieNode {
+    int32_t parent;
+    int32_t tok;
+};
+
+// Frames handled by one workgroup of the prune stage.  Survivor records of a
+// block are packed densely from the block's region base = block * fpb * V.
+__host__ __device__ inline int32_t frames_per_block(int32_t V) {
+    int32_t f = 8192 / V;
+    if (f < 1) f = 1;
+    if (f > 256) f = 256;
+    return f;
+}
+
+struct Workspace {
+    FrameHdr* hdr;      // [B*T]
+    Survivor* rec;      // [B*T*V] capacity, densely packed per frame block
+    TrieNode* trie;     // [B][trie_stride]
+    float* lm_bound;    // [1] upper bound of lm_weight*table+bonus (or 0)
+    int64_t trie_stride;
+    size_t bytes;
+};
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+inline Workspace carve_workspace(void* base, int32_t B, int32_t T, int32_t V, int32_t beam) {
+    Workspace w;
+    const size_t frames = (size_t)B * (size_t)T;
+    const size_t off_hdr = 0;
+    const size_t off_rec = align_up(off_hdr + frames * sizeof(FrameHdr), 256);
+    const size_t off_trie = align_up(off_rec + frames * (size_t)V * sizeof(Survivor), 256);
+    w.trie_stride = (int64_t)T * beam + 1;
+    const size_t off_lmb =
+        align_up(off_trie + (size_t)B * (size_t)w.trie_stride * sizeof(TrieNode), 256);
+    w.bytes = off_lmb + 256;
+    char* p = static_cast<char*>(base);
+    w.hdr = p ? reinterpret_cast<FrameHdr*>(p + off_hdr) : nullptr;
+    w.rec = p ? reinterpret_cast<Survivor*>(p + off_rec) : nullptr;
+    w.trie = p ? reinterpret_cast<TrieNode*>(p + off_trie) : nullptr;
+    w.lm_bound = p ? reinterpret_cast<float*>(p + off_lmb) : nullptr;
+    return w;
+}
+
+// Launchers (defined next to their kernels); each returns a hipError_t.
+hipError_t launch_prune(const float* logprobs, const int32_t* lengths, int32_t B, int32_t T,
+                        int32_t V, float ln_r, const Workspace& ws, hipStream_t stream);
+hipError_t launch_unpack(const Workspace& ws, int32_t B, int32_t T, int32_t V, int32_t* counts,
+                         int32_t* tokens, float* values, float* frame_max, hipStream_t stream);
+hipError_t launch_lm_bound(const float* lm_table, int32_t V, float lm_weight, float bonus,
+                           float* out, hipStream_t stream);
+hipError_t launch_beam(const float* logprobs, const int32_t* lengths, int32_t B, int32_t T,
+                       int32_t V, const fltop_params& p, const Workspace& ws, int32_t* out_tokens,
+                       int32_t* out_lengths, float* out_scores, fltop_stats* stats,
+                       hipStream_t stream);
+
+}  // namespace fltop
+#endif  // FLTOP_INTERNAL_H_

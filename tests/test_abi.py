@@ -1,0 +1,123 @@
+"""Host-side checks of the C ABI: the library loads, exports what the header declares,
+and rejects bad arguments before anything is enqueued (no GPU needed)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2510_09085_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "fltop_ctc.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2510_09085_amd import build
+        build.build()
+    return binding.load()
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(fltop_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_functions()
+    assert set(names) == set(binding.EXPORTS)
+    for name in names:
+        assert getattr(lib, name) is not None
+
+
+def test_header_constants_match_binding():
+    text = open(HEADER).read()
+    assert int(re.search(r"#define FLTOP_MAX_BEAM\s+(\d+)", text).group(1)) == binding.MAX_BEAM
+    assert int(re.search(r"#define FLTOP_MAX_VOCAB\s+(\d+)", text).group(1)) == binding.MAX_VOCAB
+    codes = dict(re.findall(r"#define (FLTOP_(?:OK|ERR_[A-Z_]+))\s+(-?\d+)", text))
+    assert codes["FLTOP_OK"] == "0"
+    assert sorted(int(v) for v in codes.values()) == list(range(-8, 1))
+
+
+def test_status_strings(lib):
+    seen = set()
+    for code in range(-8, 1):
+        s = binding.status_string(code)
+        assert s and s != "unknown status"
+        seen.add(s)
+    assert len(seen) == 9
+    assert binding.status_string(-99) == "unknown status"
+
+
+def test_workspace_bytes(lib):
+    assert binding.workspace_bytes(0, 10, 32, 8) == 0
+    assert binding.workspace_bytes(1, 0, 32, 8) == 0
+    assert binding.workspace_bytes(1, 10, 1, 8) == 0
+    assert binding.workspace_bytes(1, 10, binding.MAX_VOCAB + 1, 8) == 0
+    assert binding.workspace_bytes(1, 10, 32, 0) == 0
+    assert binding.workspace_bytes(1, 10, 32, binding.MAX_BEAM + 1) == 0
+    small = binding.workspace_bytes(1, 200, 32, 8)
+    big = binding.workspace_bytes(64, 500, 32, 32)
+    assert 0 < small < big
+    assert small % 256 == 0
+    # survivor records (8 B per token per frame) are the floor
+    assert big >= 64 * 500 * 32 * 8
+
+
+def test_argument_errors_are_reported_before_any_launch(lib):
+    """Fake non-null addresses are safe here: every call must fail in validation."""
+    fake = ctypes.c_void_p(256 * 4096)
+    p = binding.FltopParams()
+    p.beam = 8
+    p.rel_threshold = 0.01
+    need = binding.workspace_bytes(2, 10, 32, 8)
+
+    def call(lp=fake, ln=fake, B=2, T=10, V=32, params=p, ws=fake, nbytes=need, tok=fake,
+             olen=fake, sc=fake):
+        return lib.fltop_ctc_decode(lp, ln, B, T, V, ctypes.byref(params) if params else None,
+                                    ws, nbytes, tok, olen, sc, None, None)
+
+    assert call(lp=None) == -1
+    assert call(ln=None) == -1
+    assert call(params=None) == -1
+    assert call(tok=None) == -1
+    assert call(olen=None) == -1
+    assert call(sc=None) == -1
+    assert call(ws=None) == -1
+    assert call(B=0) == -2
+    assert call(T=0) == -2
+    assert call(V=1) == -2
+    assert call(V=binding.MAX_VOCAB + 1) == -6
+    assert call(nbytes=need - 1) == -5
+    assert call(ws=ctypes.c_void_p(256 * 4096 + 8)) == -8
+    for bad_beam in (0, -3, binding.MAX_BEAM + 1):
+        q = binding.FltopParams()
+        q.beam = bad_beam
+        q.rel_threshold = 0.01
+        assert call(params=q) == -3
+    for bad_r in (-0.1, 1.5, float("nan")):
+        q = binding.FltopParams()
+        q.beam = 8
+        q.rel_threshold = bad_r
+        assert call(params=q) == -4
+    q = binding.FltopParams()
+    q.beam = 8
+    q.rel_threshold = 0.5
+    q.nbest_count = 4096  # some but not all n-best pointers
+    assert call(params=q) == -1
+    # the stand-alone prune stage validates the same way
+    assert lib.fltop_ctc_prune(None, fake, 2, 10, 32, 8, 0.01, fake, need, None) == -1
+    assert lib.fltop_ctc_prune(fake, fake, 2, 10, 32, 8, 2.0, fake, need, None) == -4
+    assert lib.fltop_ctc_prune(fake, fake, 2, 10, 32, 8, 0.01, fake, 16, None) == -5
+    assert lib.fltop_ctc_unpack_survivors(fake, need, 2, 10, 32, 8, None, fake, fake, None,
+                                          None) == -1
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "nope.so"))
+    with pytest.raises(FileNotFoundError):
+        binding.load()

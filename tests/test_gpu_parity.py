@@ -1,0 +1,312 @@
+"""GPU parity: the HIP decoder against the CPU oracle, through the C ABI, on the same
+seeded inputs.  Bar: decoded tokens and lengths bit-exact, scores within 1e-4 absolute of
+the fp32-rounded oracle score, survivor lists byte-identical, integer statistics equal."""
+import itertools
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2510_09085_amd import binding, synth
+
+pytestmark = pytest.mark.gpu
+
+SCORE_TOL = 1e-4
+
+
+@pytest.fixture(scope="module")
+def dev():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    binding.load()
+    return torch.device("cuda:0")
+
+
+def gpu_decode(dev, lp, ln, beam, r, lm=None, alpha=0.0, beta=0.0, nbest=False):
+    lp_d = torch.from_numpy(np.ascontiguousarray(lp)).to(dev)
+    ln_d = torch.from_numpy(np.ascontiguousarray(ln, dtype=np.int32)).to(dev)
+    lm_d = None if lm is None else torch.from_numpy(np.ascontiguousarray(lm)).to(dev)
+    out = binding.decode(lp_d, ln_d, beam, r, lm_table=lm_d, lm_weight=alpha,
+                         insertion_bonus=beta, want_stats=True, want_nbest=nbest)
+    torch.cuda.synchronize()
+    lens = out["lengths"].cpu().numpy()
+    toks = out["tokens"].cpu().numpy()
+    res = {
+        "tokens": [toks[b, :lens[b]].tolist() for b in range(len(lens))],
+        "scores": out["scores"].cpu().numpy(),
+        "stats": binding.stats_dict(out["stats"]),
+    }
+    if nbest:
+        cnt = out["nbest_count"].cpu().numpy()
+        nt = out["nbest_tokens"].cpu().numpy()
+        nl = out["nbest_lengths"].cpu().numpy()
+        pb = out["nbest_pb"].cpu().numpy()
+        pnb = out["nbest_pnb"].cpu().numpy()
+        res["nbest"] = [[(tuple(nt[b, e, :nl[b, e]].tolist()), float(pb[b, e]), float(pnb[b, e]))
+                         for e in range(cnt[b])] for b in range(len(lens))]
+    return res
+
+
+def assert_parity(got, want_tokens, want_scores, want_stats=None, label=""):
+    for b, (g, w) in enumerate(zip(got["tokens"], want_tokens)):
+        assert g == w, f"{label}: utterance {b} tokens differ"
+    ws = np.asarray(want_scores, dtype=np.float64).astype(np.float32)
+    gs = got["scores"]
+    both_inf = np.isneginf(ws) & np.isneginf(gs)
+    assert np.all(both_inf | (np.abs(gs.astype(np.float64) - ws.astype(np.float64)) <= SCORE_TOL)), \
+        f"{label}: scores differ {gs} vs {ws}"
+    if want_stats is not None:
+        for key in ("frames", "sum_survivors", "sum_candidates", "peak_candidates", "sum_beam"):
+            assert got["stats"][key] == want_stats[key], (label, key)
+        assert got["stats"]["overflow_drops"] == 0
+
+
+def lse(a, b):
+    if a == -math.inf:
+        return b
+    if b == -math.inf:
+        return a
+    m = max(a, b)
+    return m + math.log1p(math.exp(min(a, b) - m))
+
+
+# --------------------------------------------------------------------------- prune stage
+@pytest.mark.parametrize("V", [2, 3, 5, 29, 32, 33, 64, 100, 257, 1024, 1500])
+def test_survivor_lists_are_byte_identical(dev, oracle_lib, V):
+    B, T = 3, 37
+    lp = synth.random_emissions(1000 + V, B, T, V, flat=2.5)
+    lp[1, 5, V // 2] = -np.inf
+    ln = np.array([T, 11, 0], dtype=np.int32)
+    lp[1, 11:] = np.nan
+    lp[2, :] = np.nan
+    for r in (0.0, 1e-3, 0.05, 0.5, 1.0):
+        lp_d = torch.from_numpy(lp).to(dev)
+        ln_d = torch.from_numpy(ln).to(dev)
+        ws = binding.prune(lp_d, ln_d, 4, r)
+        counts, tokens, values, fmax = [x.cpu().numpy() for x in
+                                        binding.unpack_survivors(ws, B, T, V, 4)]
+        for b in range(B):
+            n = ln[b]
+            sl = slice(b * T, b * T + n)
+            if n:
+                oc, ot, om = oracle_lib.survivors(lp[b, :n], r)
+                np.testing.assert_array_equal(counts[sl], oc)
+                np.testing.assert_array_equal(fmax[sl].view(np.uint32), om.view(np.uint32))
+                for f in range(n):
+                    k = oc[f]
+                    np.testing.assert_array_equal(tokens[b * T + f, :k], ot[f, :k])
+                    np.testing.assert_array_equal(
+                        values[b * T + f, :k].view(np.uint32),
+                        lp[b, f, ot[f, :k]].view(np.uint32))
+            assert (counts[b * T + n:(b + 1) * T] == 0).all()   # padding is skipped
+
+
+def test_survivor_lists_on_peaky_workload(dev, oracle_lib):
+    w = synth.WORKLOADS["cfg2_batch64"]
+    lp, ln = synth.make_emissions(w, utterances=range(5))
+    B, T, V = lp.shape
+    for r in w.rel_thresholds:
+        ws = binding.prune(torch.from_numpy(lp).to(dev), torch.from_numpy(ln).to(dev), w.beam, r)
+        counts, tokens, values, _ = [x.cpu().numpy() for x in
+                                     binding.unpack_survivors(ws, B, T, V, w.beam)]
+        oc, ot, _ = oracle_lib.survivors(lp, r)
+        np.testing.assert_array_equal(counts, oc)
+        mask = np.arange(V)[None, :] < oc[:, None]
+        np.testing.assert_array_equal(tokens[mask], ot[mask])
+        np.testing.assert_array_equal(values[mask].view(np.uint32),
+                                      lp.reshape(-1, V)[np.nonzero(mask)[0], ot[mask]].view(np.uint32))
+
+
+# --------------------------------------------------------------------------- small decodes
+SMALL = [
+    # B, T, V, beam
+    (4, 60, 5, 4),
+    (3, 150, 32, 8),
+    (2, 90, 33, 16),
+    (3, 70, 7, 1),
+    (2, 50, 12, 128),
+    (5, 41, 100, 31),
+]
+
+
+@pytest.mark.parametrize("B,T,V,beam", SMALL)
+@pytest.mark.parametrize("r", [0.0, 0.001, 0.05, 1.0])
+def test_small_random_decodes(dev, oracle_lib, B, T, V, beam, r):
+    lp = synth.random_emissions(7 * T + V + beam, B, T, V, flat=2.0)
+    ln = np.full(B, T, dtype=np.int32)
+    ln[-1] = T // 2 + 1
+    lp[-1, ln[-1]:] = np.nan
+    want = oracle_lib.decode(lp, ln, beam, r, n_threads=4)
+    got = gpu_decode(dev, lp, ln, beam, r)
+    assert_parity(got, want[0], want[1], want[2], f"B{B} T{T} V{V} beam{beam} r{r}")
+
+
+@pytest.mark.parametrize("r", [0.0, 0.01])
+def test_small_decode_with_bigram_lm(dev, oracle_lib, r):
+    for V, beam in ((6, 5), (32, 16), (70, 24)):
+        lp = synth.random_emissions(V * 3, 3, 80, V, flat=2.5)
+        ln = np.array([80, 33, 80], dtype=np.int32)
+        lm = synth.make_bigram_lm(V, seed=V)
+        want = oracle_lib.decode(lp, ln, beam, r, lm_table=lm, lm_weight=0.5, insertion_bonus=1.0,
+                                 n_threads=3)
+        got = gpu_decode(dev, lp, ln, beam, r, lm, 0.5, 1.0)
+        assert_parity(got, want[0], want[1], want[2], f"lm V{V} r{r}")
+
+
+def test_whole_final_beam_matches(dev, oracle_lib):
+    for seed, (T, V, beam, r) in enumerate([(40, 6, 12, 0.0), (60, 32, 20, 0.01),
+                                            (25, 9, 128, 0.0)]):
+        lp = synth.random_emissions(50 + seed, 1, T, V, flat=1.5)
+        got = gpu_decode(dev, lp, np.array([T], np.int32), beam, r, nbest=True)["nbest"][0]
+        want = oracle_lib.decode_beam(lp[0], beam, r)
+        assert [g[0] for g in got] == [w[0] for w in want]
+        for (_, gpb, gpnb), (_, wpb, wpnb) in zip(got, want):
+            for gx, wx in ((gpb, wpb), (gpnb, wpnb)):
+                assert (gx == wx) or abs(gx - wx) <= 1e-9
+
+
+def test_exhaustive_beam_against_alignment_enumeration(dev):
+    """The GPU path against brute force directly (no oracle in between): V=3, T=4 has 31
+    label strings, so beam 32 is exhaustive."""
+    T, V = 4, 3
+    for seed, r in itertools.product(range(3), (0.0, 0.3)):
+        lp = synth.random_emissions(900 + seed, 1, T, V, flat=1.5)
+        row_thr = [np.float32(lp[0, t].max() + (np.float32(np.log(np.float64(r))) if r > 0
+                                                else np.float32(-np.inf))) for t in range(T)]
+        acc = {}
+        for path in itertools.product(range(V), repeat=T):
+            if any(lp[0, t, path[t]] < row_thr[t] for t in range(T)):
+                continue
+            lab, prev = [], None
+            for s in path:
+                if s != prev and s != 0:
+                    lab.append(s)
+                prev = s
+            sc = sum(float(lp[0, t, path[t]]) for t in range(T))
+            acc[tuple(lab)] = lse(acc.get(tuple(lab), -math.inf), sc)
+        got = gpu_decode(dev, lp, np.array([T], np.int32), 32, r, nbest=True)["nbest"][0]
+        assert {g[0] for g in got} == set(acc)
+        for toks, pb, pnb in got:
+            assert lse(pb, pnb) == pytest.approx(acc[toks], abs=1e-11)
+
+
+# --------------------------------------------------------------------------- degenerate cases
+def test_one_hot_rows_and_dead_utterances(dev, oracle_lib):
+    rng = np.random.default_rng(3)
+    T, V = 50, 7
+    path = rng.integers(0, V, size=(3, T))
+    lp = np.full((3, T, V), -np.inf, dtype=np.float32)
+    for b in range(3):
+        lp[b, np.arange(T), path[b]] = 0.0
+    lp[2, 20, :] = -np.inf    # no mass at all on this frame: every route dies
+    ln = np.array([T, 0, T], dtype=np.int32)
+    for r in (0.0, 0.01, 1.0):
+        for beam in (1, 4):
+            want = oracle_lib.decode(lp, ln, beam, r)
+            got = gpu_decode(dev, lp, ln, beam, r)
+            assert_parity(got, want[0], want[1], want[2], f"one-hot r{r} beam{beam}")
+            assert got["scores"][0] == 0.0 and got["scores"][1] == 0.0
+            assert np.isneginf(got["scores"][2]) and got["tokens"][2] == []
+
+
+def test_exact_ties_use_the_hash_order(dev, oracle_lib):
+    """Uniform rows: many candidates tie exactly; V=200 forces the tie group past the
+    exact-ranking capacity, so the hash-window path runs too."""
+    for V, T, beam in ((6, 3, 4), (40, 2, 7), (200, 2, 9), (200, 3, 128)):
+        lp = np.full((1, T, V), -math.log(V), dtype=np.float32)
+        ln = np.array([T], np.int32)
+        want = oracle_lib.decode_beam(lp[0], beam, 0.0)
+        got = gpu_decode(dev, lp, ln, beam, 0.0, nbest=True)
+        assert {g[0] for g in got["nbest"][0]} == {w[0] for w in want}, (V, T, beam)
+        assert got["stats"]["overflow_drops"] == 0
+
+
+def test_beam_one_threshold_one_is_argmax_path(dev, oracle_lib):
+    lp = synth.random_emissions(11, 3, 80, 9, flat=3.0)
+    ln = np.array([80, 80, 41], dtype=np.int32)
+    got = gpu_decode(dev, lp, ln, 1, 1.0)
+    for b in range(3):
+        rows = lp[b, :ln[b]]
+        am = rows.argmax(axis=1)
+        lab = [int(s) for i, s in enumerate(am) if s != 0 and (i == 0 or am[i - 1] != s)]
+        assert got["tokens"][b] == lab
+        assert got["scores"][b] == pytest.approx(float(rows.max(axis=1).astype(np.float64).sum()),
+                                                 abs=SCORE_TOL)
+
+
+def test_single_frame_and_repeatability(dev, oracle_lib):
+    lp = synth.random_emissions(5, 2, 1, 32)
+    ln = np.array([1, 1], np.int32)
+    want = oracle_lib.decode(lp, ln, 8, 0.0)
+    assert_parity(gpu_decode(dev, lp, ln, 8, 0.0), want[0], want[1], want[2], "T=1")
+    w = synth.WORKLOADS["cfg1_single"]
+    lp, ln = synth.make_emissions(w)
+    a = gpu_decode(dev, lp, ln, w.beam, 0.01)
+    b = gpu_decode(dev, lp, ln, w.beam, 0.01)
+    assert a["tokens"] == b["tokens"]
+    assert a["scores"].tobytes() == b["scores"].tobytes()
+    assert a["stats"] == b["stats"]
+
+
+def test_bad_arguments_raise(dev):
+    lp = torch.zeros((2, 4, 8), device=dev)
+    ln = torch.full((2,), 4, dtype=torch.int32, device=dev)
+    with pytest.raises(binding.FltopError) as e:
+        binding.decode(lp, ln, 8, 1.5)
+    assert e.value.status == -4
+    with pytest.raises(binding.FltopError) as e:
+        binding.decode(lp, ln, 8, 0.1, workspace=torch.empty(256, dtype=torch.uint8, device=dev))
+    assert e.value.status == -5
+    with pytest.raises(ValueError):
+        binding.decode(lp.cpu(), ln.cpu(), 8, 0.1)
+
+
+# --------------------------------------------------------------------------- the five workloads
+def _check_workload(dev, oracle_lib, name, r, sample, threads=8):
+    """GPU decodes the whole batch in its benchmark launch shape; the oracle decodes a
+    sample of the utterances (utterances are independent), all of them when cheap."""
+    w = synth.WORKLOADS[name]
+    lp, ln = synth.make_emissions(w)
+    lm = synth.make_bigram_lm(w.V) if w.use_lm else None
+    got = gpu_decode(dev, lp, ln, w.beam, r, lm, w.lm_weight, w.insertion_bonus)
+    idx = list(range(w.B)) if sample is None else sample
+    want = oracle_lib.decode(lp[idx], ln[idx], w.beam, r, lm_table=lm, lm_weight=w.lm_weight,
+                             insertion_bonus=w.insertion_bonus, n_threads=threads)
+    sub = {"tokens": [got["tokens"][i] for i in idx], "scores": got["scores"][idx],
+           "stats": got["stats"]}
+    assert_parity(sub, want[0], want[1], want[2] if sample is None else None, f"{name} r={r}")
+    assert got["stats"]["frames"] == int(ln.sum())
+    assert got["stats"]["overflow_drops"] == 0
+    return got, want
+
+
+@pytest.mark.parametrize("r", [0.01, 0.0])
+def test_workload_cfg1(dev, oracle_lib, r):
+    _check_workload(dev, oracle_lib, "cfg1_single", r, None)
+
+
+@pytest.mark.parametrize("r", [0.1, 0.01, 0.001, 0.0])
+def test_workload_cfg2(dev, oracle_lib, r):
+    _check_workload(dev, oracle_lib, "cfg2_batch64", r, None if r > 0 else list(range(0, 64, 4)))
+
+
+def test_workload_cfg3(dev, oracle_lib):
+    w = synth.WORKLOADS["cfg3_varlen256"]
+    ln = synth.make_lengths(w)
+    order = np.argsort(ln)
+    sample = sorted({int(order[0]), int(order[-1]), int(order[len(order) // 2]), 3, 77, 200})
+    _check_workload(dev, oracle_lib, "cfg3_varlen256", 0.01, sample)
+
+
+def test_workload_cfg4_pruned(dev, oracle_lib):
+    _check_workload(dev, oracle_lib, "cfg4_subword1024", 0.01, list(range(0, 128, 16)))
+
+
+def test_workload_cfg4_unpruned(dev, oracle_lib):
+    _check_workload(dev, oracle_lib, "cfg4_subword1024", 0.0, [5])
+
+
+@pytest.mark.parametrize("r", [0.01, 0.0])
+def test_workload_cfg5(dev, oracle_lib, r):
+    _check_workload(dev, oracle_lib, "cfg5_bigram_lm", r,
+                    list(range(0, 128, 8)) if r > 0 else [0, 64])

@@ -125,6 +125,17 @@ int fltop_ctc_prune(const float* logprobs, const int32_t* lengths,
                     int32_t B, int32_t T, int32_t V, int32_t beam, float rel_threshold,
                     void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* The second stage alone (Algorithm 1's loop over beam entries and kept tokens,
+ * SelectTopK and GetHighestScorePrefix) over survivor lists that fltop_ctc_prune
+ * left in `workspace` for the same logprobs, lengths, shapes and beam.
+ * fltop_ctc_decode is exactly fltop_ctc_prune followed by this call; the split
+ * exists so that each stage can be timed and tested by itself.  Argument rules as
+ * for fltop_ctc_decode; params->rel_threshold is not used here. */
+int fltop_ctc_search(const int32_t* lengths, int32_t B, int32_t T, int32_t V,
+                     const fltop_params* params, void* workspace, size_t workspace_bytes,
+                     int32_t* out_tokens, int32_t* out_lengths, float* out_scores,
+                     fltop_stats* stats, void* hip_stream);
+
 /* Copy the survivor lists fltop_ctc_prune left in `workspace` into plain
  * arrays: counts dev [B*T] int32 (0 for frames beyond the length), tokens dev
  * [B*T,V] int32 and values dev [B*T,V] fp32 (first counts[f] entries of row f,

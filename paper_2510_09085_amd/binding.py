@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_PKG, "libfltop_ctc.so")
 MAX_BEAM = 128
 MAX_VOCAB = 4096
 
-EXPORTS = ("fltop_ctc_workspace_bytes", "fltop_ctc_decode", "fltop_ctc_prune",
+EXPORTS = ("fltop_ctc_workspace_bytes", "fltop_ctc_decode", "fltop_ctc_prune", "fltop_ctc_search",
            "fltop_ctc_unpack_survivors", "fltop_status_string")
 
 
@@ -63,6 +63,9 @@ def load():
     lib.fltop_ctc_workspace_bytes.argtypes = [i32, i32, i32, i32]
     lib.fltop_ctc_decode.restype = ctypes.c_int
     lib.fltop_ctc_decode.argtypes = [vp, vp, i32, i32, i32, ctypes.POINTER(FltopParams), vp, sz,
+                                     vp, vp, vp, vp, vp]
+    lib.fltop_ctc_search.restype = ctypes.c_int
+    lib.fltop_ctc_search.argtypes = [vp, i32, i32, i32, ctypes.POINTER(FltopParams), vp, sz,
                                      vp, vp, vp, vp, vp]
     lib.fltop_ctc_prune.restype = ctypes.c_int
     lib.fltop_ctc_prune.argtypes = [vp, vp, i32, i32, i32, i32, f32, vp, sz, vp]
@@ -118,6 +121,25 @@ def decode_raw(logprobs, lengths, params: FltopParams, workspace, workspace_nbyt
                                        ctypes.byref(params), _ptr(workspace), workspace_nbytes,
                                        _ptr(out_tokens), _ptr(out_lengths), _ptr(out_scores),
                                        _ptr(stats), _stream_handle(stream)))
+
+
+def search_raw(lengths, shape, params: FltopParams, workspace, workspace_nbytes, out_tokens,
+               out_lengths, out_scores, stats, stream=None) -> int:
+    """Direct call of fltop_ctc_search on a workspace fltop_ctc_prune has filled."""
+    B, T, V = shape
+    return int(load().fltop_ctc_search(_ptr(lengths), B, T, V, ctypes.byref(params),
+                                       _ptr(workspace), workspace_nbytes, _ptr(out_tokens),
+                                       _ptr(out_lengths), _ptr(out_scores), _ptr(stats),
+                                       _stream_handle(stream)))
+
+
+def prune_raw(logprobs, lengths, beam, rel_threshold, workspace, workspace_nbytes,
+              stream=None) -> int:
+    """Direct call of fltop_ctc_prune; returns the status code."""
+    B, T, V = logprobs.shape
+    return int(load().fltop_ctc_prune(_ptr(logprobs), _ptr(lengths), B, T, V, int(beam),
+                                      float(rel_threshold), _ptr(workspace), workspace_nbytes,
+                                      _stream_handle(stream)))
 
 
 def decode(logprobs: torch.Tensor, lengths: torch.Tensor, beam: int, rel_threshold: float, *,

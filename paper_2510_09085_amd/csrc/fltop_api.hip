@@ -70,6 +70,51 @@ extern "C" int fltop_ctc_unpack_survivors(const void* workspace, size_t workspac
     return e == hipSuccess ? FLTOP_OK : FLTOP_ERR_HIP;
 }
 
+namespace {
+
+int check_nbest(const fltop_params* p) {
+    const bool any = p->nbest_count || p->nbest_tokens || p->nbest_lengths || p->nbest_pb ||
+                     p->nbest_pnb;
+    const bool all = p->nbest_count && p->nbest_tokens && p->nbest_lengths && p->nbest_pb &&
+                     p->nbest_pnb;
+    return (any && !all) ? FLTOP_ERR_NULL_POINTER : FLTOP_OK;
+}
+
+int enqueue_search(const int32_t* lengths, int32_t B, int32_t T, int32_t V,
+                   const fltop_params* params, const fltop::Workspace& ws, int32_t* out_tokens,
+                   int32_t* out_lengths, float* out_scores, fltop_stats* stats,
+                   hipStream_t stream) {
+    hipError_t e = hipSuccess;
+    if (params->lm_table) {
+        e = fltop::launch_lm_bound(params->lm_table, V, params->lm_weight, params->insertion_bonus,
+                                   ws.lm_bound, stream);
+        if (e != hipSuccess) return FLTOP_ERR_HIP;
+    }
+    e = fltop::launch_beam(lengths, B, T, V, *params, ws, out_tokens, out_lengths, out_scores,
+                           stats, stream);
+    return e == hipSuccess ? FLTOP_OK : FLTOP_ERR_HIP;
+}
+
+}  // namespace
+
+extern "C" int fltop_ctc_search(const int32_t* lengths, int32_t B, int32_t T, int32_t V,
+                                const fltop_params* params, void* workspace,
+                                size_t workspace_bytes, int32_t* out_tokens, int32_t* out_lengths,
+                                float* out_scores, fltop_stats* stats, void* hip_stream) {
+    if (!lengths || !params || !out_tokens || !out_lengths || !out_scores)
+        return FLTOP_ERR_NULL_POINTER;
+    int rc = check_shapes(B, T, V, params->beam);
+    if (rc != FLTOP_OK) return rc;
+    rc = check_nbest(params);
+    if (rc != FLTOP_OK) return rc;
+    rc = check_workspace(workspace, workspace_bytes,
+                         fltop_ctc_workspace_bytes(B, T, V, params->beam));
+    if (rc != FLTOP_OK) return rc;
+    const fltop::Workspace ws = fltop::carve_workspace(workspace, B, T, V, params->beam);
+    return enqueue_search(lengths, B, T, V, params, ws, out_tokens, out_lengths, out_scores, stats,
+                          static_cast<hipStream_t>(hip_stream));
+}
+
 extern "C" int fltop_ctc_decode(const float* logprobs, const int32_t* lengths, int32_t B, int32_t T,
                                 int32_t V, const fltop_params* params, void* workspace,
                                 size_t workspace_bytes, int32_t* out_tokens, int32_t* out_lengths,
@@ -80,11 +125,8 @@ extern "C" int fltop_ctc_decode(const float* logprobs, const int32_t* lengths, i
     if (rc != FLTOP_OK) return rc;
     rc = check_threshold(params->rel_threshold);
     if (rc != FLTOP_OK) return rc;
-    const bool any_nbest = params->nbest_count || params->nbest_tokens || params->nbest_lengths ||
-                           params->nbest_pb || params->nbest_pnb;
-    const bool all_nbest = params->nbest_count && params->nbest_tokens && params->nbest_lengths &&
-                           params->nbest_pb && params->nbest_pnb;
-    if (any_nbest && !all_nbest) return FLTOP_ERR_NULL_POINTER;
+    rc = check_nbest(params);
+    if (rc != FLTOP_OK) return rc;
     rc = check_workspace(workspace, workspace_bytes,
                          fltop_ctc_workspace_bytes(B, T, V, params->beam));
     if (rc != FLTOP_OK) return rc;
@@ -94,14 +136,8 @@ extern "C" int fltop_ctc_decode(const float* logprobs, const int32_t* lengths, i
     hipError_t e = fltop::launch_prune(logprobs, lengths, B, T, V,
                                        ln_threshold(params->rel_threshold), ws, stream);
     if (e != hipSuccess) return FLTOP_ERR_HIP;
-    if (params->lm_table) {
-        e = fltop::launch_lm_bound(params->lm_table, V, params->lm_weight, params->insertion_bonus,
-                                   ws.lm_bound, stream);
-        if (e != hipSuccess) return FLTOP_ERR_HIP;
-    }
-    e = fltop::launch_beam(logprobs, lengths, B, T, V, *params, ws, out_tokens, out_lengths,
-                           out_scores, stats, stream);
-    return e == hipSuccess ? FLTOP_OK : FLTOP_ERR_HIP;
+    return enqueue_search(lengths, B, T, V, params, ws, out_tokens, out_lengths, out_scores, stats,
+                          stream);
 }
 
 extern "C" const char* fltop_status_string(int status) {

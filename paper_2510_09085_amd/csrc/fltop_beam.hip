@@ -647,11 +647,10 @@ __global__ __launch_bounds__(kThreads) void beam_kernel(BeamArgs a) {
 
 }  // namespace
 
-hipError_t launch_beam(const float* logprobs, const int32_t* lengths, int32_t B, int32_t T,
-                       int32_t V, const fltop_params& p, const Workspace& ws, int32_t* out_tokens,
+hipError_t launch_beam(const int32_t* lengths, int32_t B, int32_t T, int32_t V,
+                       const fltop_params& p, const Workspace& ws, int32_t* out_tokens,
                        int32_t* out_lengths, float* out_scores, fltop_stats* stats,
                        hipStream_t stream) {
-    (void)logprobs;
     BeamArgs a;
     a.lengths = lengths;
     a.hdr = ws.hdr;

@@ -75,8 +75,8 @@ hipError_t launch_unpack(const Workspace& ws, int32_t B, int32_t T, int32_t V, i
                          int32_t* tokens, float* values, float* frame_max, hipStream_t stream);
 hipError_t launch_lm_bound(const float* lm_table, int32_t V, float lm_weight, float bonus,
                            float* out, hipStream_t stream);
-hipError_t launch_beam(const float* logprobs, const int32_t* lengths, int32_t B, int32_t T,
-                       int32_t V, const fltop_params& p, const Workspace& ws, int32_t* out_tokens,
+hipError_t launch_beam(const int32_t* lengths, int32_t B, int32_t T, int32_t V,
+                       const fltop_params& p, const Workspace& ws, int32_t* out_tokens,
                        int32_t* out_lengths, float* out_scores, fltop_stats* stats,
                        hipStream_t stream);
 

@@ -109,8 +109,14 @@ def event_times_ms(torch, fn, reps, warm=2):
 
 
 def prune_bytes(w, stats):
-    """Algorithmic bytes of one prune launch: emission read + header and record writes."""
-    return 4 * w.V * stats["frames"] + 16 * stats["frames"] + 8 * stats["sum_survivors"]
+    """Algorithmic bytes of one prune launch: the fp32 emissions of every valid frame.
+    (What the stage writes -- a 64-byte header per frame and 8 bytes per survivor -- is
+    reported beside it, not counted.)"""
+    return 4 * w.V * stats["frames"]
+
+
+def prune_written_bytes(stats):
+    return 64 * stats["frames"] + 8 * stats["sum_survivors"]
 
 
 def emission_read_roofline(torch, binding, synth, w, r, dev, target_bytes=1 << 30, reps=20):
@@ -128,7 +134,7 @@ def emission_read_roofline(torch, binding, synth, w, r, dev, target_bytes=1 << 3
             "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4),
             "traffic": None, "kernel": "prune", "avg_launch_us": round(avg * 1e3, 2),
             "min_launch_us": round(min(ms) * 1e3, 2), "algorithmic_bytes": nbytes,
-            "rotated_copies": copies}
+            "written_bytes": prune_written_bytes(st), "rotated_copies": copies}
 
 
 def cpu_baseline(synth, w, r, frames_budget_s=12.0):
@@ -242,7 +248,7 @@ def main():
                 "mean_candidates": round(s["sum_candidates"] / s["frames"], 2),
                 "peak_candidates": s["peak_candidates"],
                 "peak_candidate_bytes": s["peak_candidates"] * CAND_RECORD_BYTES,
-                "survivor_record_bytes": 16 * s["frames"] + 8 * s["sum_survivors"],
+                "survivor_record_bytes": prune_written_bytes(s),
                 "select_passes_per_frame": round(s["select_passes"] / s["frames"], 3),
                 "exact_rankings_per_frame": round(s["exact_rankings"] / s["frames"], 3),
             })

@@ -13,7 +13,7 @@ from typing import Optional
 import torch
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_PKG, "libfltop_ctc.so")
+LIB_PATH = os.environ.get("FLTOP_CTC_LIB") or os.path.join(_PKG, "libfltop_ctc.so")
 
 MAX_BEAM = 128
 MAX_VOCAB = 4096
@@ -38,7 +38,8 @@ class FltopParams(ctypes.Structure):
 
 
 STATS_FIELDS = ("frames", "sum_survivors", "sum_candidates", "peak_candidates", "sum_beam",
-                "select_passes", "exact_rankings", "overflow_drops")
+                "select_passes", "exact_rankings", "overflow_drops",
+                "clk0", "clk1", "clk2", "clk3", "clk4", "clk5", "clk6", "clk7")
 
 _lib = None
 

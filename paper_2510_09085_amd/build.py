@@ -17,12 +17,13 @@ HIPCC_FLAGS = [
 ]
 
 
-def build(verbose: bool = False) -> str:
+def build(verbose: bool = False, out: str = LIB_PATH, defines=()) -> str:
     """Always recompiles; returns the path of the shared library."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     srcs = sorted(glob.glob(os.path.join(_PKG, "csrc", "*.hip")))
-    cmd = [hipcc, *HIPCC_FLAGS, "-I", os.path.join(_ROOT, "include"),
-           "-I", os.path.join(_PKG, "csrc"), *srcs, "-o", LIB_PATH]
+    cmd = [hipcc, *HIPCC_FLAGS, *[f"-D{d}" for d in defines],
+           "-I", os.path.join(_ROOT, "include"),
+           "-I", os.path.join(_PKG, "csrc"), *srcs, "-o", out]
     if verbose:
         print(" ".join(cmd))
     subprocess.run(cmd, check=True)

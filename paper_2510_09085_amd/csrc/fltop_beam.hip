@@ -4,18 +4,28 @@
 //
 // One workgroup decodes one utterance and stays resident for all its frames.
 // The beam (prefix hash, parent hash, last token, p_b, p_nb, trie node) lives in
-// LDS.  Candidates are never materialised: a candidate is either "entry j stays"
-// or "entry i extended by survivor k", and its score is recomputed from the
-// LDS-resident beam whenever a pass needs it.  An extension i+s can only
+// LDS.  A candidate is either "entry j stays" or "entry i extended by survivor
+// k"; candidates are held in registers (or recomputed when there are more than
+// the registers hold), never written to memory.  An extension i+s can only
 // coincide with a prefix that is already in the beam (a prefix has one parent),
-// so merging is done from the side of that beam entry: it looks its parent up
-// in an LDS hash table and adds the parent's extension mass to its own p_nb;
-// the extension itself is then skipped.  Every log-sum-exp has two operands.
+// so merging is done from the side of that beam entry: it finds its parent
+// through an LDS hash table and adds the parent's extension mass to its own
+// p_nb; the extension itself is then skipped.  Every log-sum-exp has two operands.
 //
 // Top-`beam` selection works on an order-preserving 64-bit image of the fp64
-// score: a histogram over the distance to an upper bound locates the bucket
-// holding the beam-th best candidate, buckets are refined until the boundary
-// bucket is small, and its members are ranked exactly by (score, prefix hash).
+// score: a two-level histogram over the distance to an upper bound locates the
+// bucket holding the beam-th best candidate, buckets are refined until the
+// boundary bucket is small, and its members are ranked exactly by (score, hash).
+//
+// Latency is what matters here (frames of one utterance are strictly serial):
+//  - frame headers (which carry the first six survivors) are staged through LDS
+//    32 frames at a time, one chunk ahead, and barriers wait for LDS traffic only,
+//    so global loads and trie stores stay in flight across them;
+//  - frames whose only survivor is blank change no prefix and no order: every
+//    entry just adds the blank log-prob, with no barrier at all;
+//  - frames with at most six survivors keep them in registers;
+//  - "stay" candidates (which need the log-sum-exps) and extension candidates are
+//    mapped to different wavefronts so that they are evaluated side by side.
 #include "fltop_internal.h"
 
 namespace fltop {
@@ -25,10 +35,14 @@ constexpr int kThreads = 256;
 constexpr int kWave = 64;
 constexpr int kMaxBeam = FLTOP_MAX_BEAM;
 constexpr int kHashSlots = 4 * kMaxBeam;
-constexpr int kBins = 1024;
-constexpr int kBinsPerLane = kBins / kWave;  // 16
+constexpr int kFine = 1024;  // histogram bins
+constexpr int kCoarse = 64;  // one per lane; a coarse bin covers 16 fine bins
 constexpr int kExactCap = 64;
-constexpr int kMaxShift = 54;  // kBins << kMaxShift covers all 64-bit distances
+constexpr int kMaxShift = 54;  // kFine << kMaxShift covers all 64-bit distances
+constexpr int kRegK = kInlineSurvivors;  // survivors kept in registers
+constexpr int kRegCand = 2;              // extension candidates cached per thread
+constexpr int kChunk = 32;               // frame headers staged per chunk
+constexpr int kWaypoints = 256;
 constexpr uint64_t kGolden = 0x9E3779B97F4A7C15ull;
 constexpr uint64_t kAllOnes = ~0ull;
 
@@ -41,6 +55,16 @@ struct BeamSlab {
     int32_t last[kMaxBeam];  // last token, -1 for the empty prefix
     int32_t node[kMaxBeam];  // trie node of the prefix
     int32_t plen[kMaxBeam];  // prefix length
+    int32_t xanc[kMaxBeam];  // trie node of the ancestor at depth 8*floor(plen/8)
+};
+
+// parent / children links of one beam generation
+struct Links {
+    int32_t par[kMaxBeam];
+    int32_t first_kid[kMaxBeam];
+    int32_t next_kid[kMaxBeam];
+    uint32_t kidmask[kMaxBeam];  // bit (token & 31) set for every child in the beam
+    int32_t ht[kHashSlots];      // open addressing: slot -> beam index, keyed by prefix hash
 };
 
 struct BeamArgs {
@@ -52,7 +76,7 @@ struct BeamArgs {
     const float* lm_table;  // global copy (always valid when LM is on)
     const float* lm_bound;
     double lm_alpha, lm_beta;
-    int32_t B, T, V, fpb, beam;
+    int32_t B, T, V, pg_shift, beam;
     int32_t lm_in_lds;  // 1: table staged into LDS
     int32_t* out_tokens;
     int32_t* out_lengths;
@@ -99,10 +123,6 @@ __device__ inline int lanes_below(uint64_t mask, int lane) {
     return __popcll(mask & ((1ull << lane) - 1ull));
 }
 
-// bin b is stored transposed so that lane l of a wave owns bins [16l, 16l+16)
-// at conflict-free addresses (q*64 + l).
-__device__ inline int bin_slot(int b) { return (b & (kBinsPerLane - 1)) * kWave + (b >> 4); }
-
 __device__ inline uint64_t sat_add(uint64_t a, uint64_t b) {
     const uint64_t s = a + b;
     return s < a ? kAllOnes : s;
@@ -115,20 +135,305 @@ __device__ inline uint64_t bucket_top(uint64_t lo, int b, int sh) {
     return sat_add(lo, (nb << sh) - 1ull);
 }
 
+// Workgroup barrier that orders LDS traffic only: global loads and stores issued
+// earlier (header chunks, survivor records, trie nodes) stay in flight across it.
+__device__ __forceinline__ void lds_barrier() {
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// Value of `v` in the lane selected by a DPP control word, 0 where that lane does
+// not exist or the row is masked off.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ int dpp_or_zero(int v) {
+    return __builtin_amdgcn_update_dpp(0, v, CTRL, ROW_MASK, 0xf, false);
+}
+
+// Inclusive prefix sum inside each row of 16 lanes (row_shr 1,2,3 then 4 and 8).
+__device__ __forceinline__ int row_inclusive_scan(int v0) {
+    int v1 = v0 + dpp_or_zero<0x111, 0xf>(v0);
+    v1 += dpp_or_zero<0x112, 0xf>(v0);
+    v1 += dpp_or_zero<0x113, 0xf>(v0);
+    v1 += dpp_or_zero<0x114, 0xf>(v1);
+    v1 += dpp_or_zero<0x118, 0xf>(v1);
+    return v1;
+}
+
+// Inclusive prefix sum over the 64 lanes: row scans, then lane 15 of a row is
+// broadcast into the next row (rows 1 and 3), then lane 31 into rows 2 and 3.
+__device__ __forceinline__ int wave_inclusive_scan(int v0) {
+    int v1 = row_inclusive_scan(v0);
+    v1 += dpp_or_zero<0x142, 0xa>(v1);
+    v1 += dpp_or_zero<0x143, 0xc>(v1);
+    return v1;
+}
+
 // dynamic LDS: dense_lp[V] fp32, s_tok[V] u16, then (optionally) the LM table
 __host__ __device__ inline size_t lm_lds_offset(int V) {
     return (((size_t)V * (sizeof(float) + sizeof(uint16_t))) + 15) / 16 * 16;
 }
 
+// Optional per-phase cycle accounting (thread 0 of every workgroup), compiled in only
+// with -DFLTOP_PHASE_CLOCKS; the default build carries none of it.
+#ifdef FLTOP_PHASE_CLOCKS
+#define PHASE_MARK(idx)                      \
+    do {                                     \
+        if (tid == 0) {                      \
+            const uint64_t now_ = clock64(); \
+            ph_clk[idx] += now_ - ph_last;   \
+            ph_last = now_;                  \
+        }                                    \
+    } while (0)
+#else
+#define PHASE_MARK(idx) \
+    do {                \
+    } while (0)
+#endif
+
+// What a frame header holds besides survivors 2..5 (one 32-byte LDS read).
+struct HdrHead {
+    int32_t count;
+    uint32_t offset;
+    float top;
+    int32_t pad;
+    Survivor s0, s1;
+};
+
+// An LDS-typed pointer: reads through it are LDS reads, not generic (flat) ones, which
+// would wait on the global-memory counter as well.
+typedef const __attribute__((address_space(3))) float* LdsFloatPtr;
+
+// Uniform per-frame values the candidate evaluation needs.  Only ever read through
+// constant field names, so it dissolves into registers after inlining.
+struct FrameCtx {
+    const BeamSlab* cur;
+    const Links* lk;
+    const float* dense_lp;   // LDS, K > 6 only: log-prob by token, -inf if pruned
+    const uint16_t* s_tok;   // LDS, K > 6 only: surviving tokens, ascending
+    LdsFloatPtr lm_lds;      // LM table staged in LDS (kernel variant kLmLds)
+    const float* lm_glb;     // LM table in global memory (kernel variant kLmGlobal)
+    double lm_alpha, lm_beta;
+    int V;
+    bool big;                // survivors staged through LDS
+    int nb0;                 // 1 if blank survived (it is record 0 then)
+    int Knb;                 // non-blank survivors
+    uint32_t div_magic;      // ceil(2^32 / Knb) for e / Knb
+    uint64_t Rk;             // key of an upper bound of every candidate score
+    // survivors 0..5 as plain scalars (an indexed private array would live in scratch)
+    int32_t t0, t1, t2, t3, t4, t5;
+    float l0, l1, l2, l3, l4, l5;
+};
+
+// Selection window: bucket(x) = (x - lo) >> sh over score distances (mode 0) or over
+// prefix hashes of the candidates whose distance is exactly Dfix (mode 1).
+struct Window {
+    uint64_t lo, Dfix;
+    int sh, mode;
+};
+
+// The register-resident survivors travel by value (twelve scalars): selecting among
+// fields read through a pointer would be turned into an indexed load, i.e. scratch.
+__device__ __forceinline__ int32_t pick_tok(int k, int32_t t0, int32_t t1, int32_t t2, int32_t t3,
+                                            int32_t t4, int32_t t5) {
+    int32_t r = t0;
+    r = (k == 1) ? t1 : r;
+    r = (k == 2) ? t2 : r;
+    r = (k == 3) ? t3 : r;
+    r = (k == 4) ? t4 : r;
+    r = (k == 5) ? t5 : r;
+    return r;
+}
+
+__device__ __forceinline__ float pick_lp(int32_t tok, int32_t t0, int32_t t1, int32_t t2,
+                                         int32_t t3, int32_t t4, int32_t t5, float l0, float l1,
+                                         float l2, float l3, float l4, float l5) {
+    float r = -INFINITY;
+    r = (t0 == tok) ? l0 : r;
+    r = (t1 == tok) ? l1 : r;
+    r = (t2 == tok) ? l2 : r;
+    r = (t3 == tok) ? l3 : r;
+    r = (t4 == tok) ? l4 : r;
+    r = (t5 == tok) ? l5 : r;
+    return r;
+}
+
+__device__ __forceinline__ int32_t surv_tok(const FrameCtx& f, int k) {
+    if (f.big) return (int32_t)f.s_tok[k];
+    const int32_t t0 = f.t0, t1 = f.t1, t2 = f.t2, t3 = f.t3, t4 = f.t4, t5 = f.t5;
+    return pick_tok(k, t0, t1, t2, t3, t4, t5);
+}
+
+// log-prob of a token in this frame, -inf when it did not survive (or tok < 0)
+__device__ __forceinline__ double lp_of(const FrameCtx& f, int32_t tok) {
+    if (tok < 0) return -INFINITY;
+    if (f.big) return (double)f.dense_lp[tok];
+    const int32_t t0 = f.t0, t1 = f.t1, t2 = f.t2, t3 = f.t3, t4 = f.t4, t5 = f.t5;
+    const float l0 = f.l0, l1 = f.l1, l2 = f.l2, l3 = f.l3, l4 = f.l4, l5 = f.l5;
+    return (double)pick_lp(tok, t0, t1, t2, t3, t4, t5, l0, l1, l2, l3, l4, l5);
+}
+
+// The LM flavour is a kernel template parameter: with one kernel serving all three, the
+// LDS read and the global read would meet at a joint wait on both memory counters.
+enum : int { kLmNone = 0, kLmLds = 1, kLmGlobal = 2 };
+
+template <int LM>
+__device__ __forceinline__ double lm_term(const FrameCtx& f, int32_t prev, int32_t tok) {
+    if (LM == kLmNone) return 0.0;
+    const int32_t row = prev < 0 ? 0 : prev;
+    const int64_t at = (int64_t)row * f.V + tok;
+    const float v = (LM == kLmLds) ? f.lm_lds[at] : f.lm_glb[at];
+    return f.lm_alpha * (double)v + f.lm_beta;
+}
+
+// Extension candidate e = i * Knb + k (entry i, non-blank survivor k): distance of its
+// score below the reference, or ~0 when it has no mass or coincides with a beam entry
+// (that entry's own update absorbs it).
+template <int LM>
+__device__ __forceinline__ uint64_t eval_ext(const FrameCtx& f, int e, int& src_entry,
+                                             int32_t& tok) {
+    const int i = f.Knb > 1 ? (int)__umulhi((uint32_t)e, f.div_magic) : e;
+    const int k = e - i * f.Knb;
+    const int32_t s = surv_tok(f, f.nb0 + k);
+    src_entry = i;
+    tok = s;
+    const int32_t li = f.cur->last[i];
+    if ((f.lk->kidmask[i] >> (s & 31)) & 1u) {  // maybe a child i+s is in the beam
+        int guard = 0;
+        for (int kid = f.lk->first_kid[i]; kid >= 0 && guard < kMaxBeam;
+             kid = f.lk->next_kid[kid], ++guard)
+            if (f.cur->last[kid] == s) return kAllOnes;
+    }
+    const double src = (s == li) ? f.cur->pb[i] : f.cur->ptot[i];
+    const double sc = src + lp_of(f, s) + lm_term<LM>(f, li, s);
+    if (!(sc > -INFINITY)) return kAllOnes;
+    return f.Rk - order_key(sc);
+}
+
+__device__ __forceinline__ uint64_t cand_hash(const FrameCtx& f, int src_entry, int32_t tok) {
+    const uint64_t h = f.cur->h[src_entry];
+    return tok < 0 ? h : child_hash(h, tok);
+}
+
+__device__ __forceinline__ int window_bin(const Window& w, uint64_t x) {
+    const uint64_t q = (x - w.lo) >> w.sh;
+    return q > (uint64_t)(kFine - 1) ? (kFine - 1) : (int)q;
+}
+
+// One candidate into the two-level histogram of the current window.
+__device__ __forceinline__ void hist_add(const FrameCtx& f, const Window& w, uint64_t D, int se,
+                                         int32_t tk, uint32_t* hfine, uint32_t* hcoarse) {
+    uint64_t x = D;
+    if (w.mode != 0) {
+        if (D != w.Dfix) return;
+        x = cand_hash(f, se, tk);
+    }
+    if (x < w.lo) return;
+    const int bin = window_bin(w, x);
+    atomicAdd(&hfine[bin], 1u);
+    atomicAdd(&hcoarse[bin >> 4], 1u);
+}
+
+// One candidate into the boundary list if it falls into bucket `bstar`.
+__device__ __forceinline__ void boundary_add(const FrameCtx& f, const Window& w, int bstar,
+                                             uint64_t D, int se, int32_t tk, int32_t* count,
+                                             uint64_t* bl_D, uint64_t* bl_h) {
+    uint64_t x = D;
+    uint64_t hh = 0;
+    bool have_h = false;
+    if (w.mode != 0) {
+        if (D != w.Dfix) return;
+        hh = cand_hash(f, se, tk);
+        have_h = true;
+        x = hh;
+    }
+    if (x < w.lo) return;
+    if (window_bin(w, x) != bstar) return;
+    if (!have_h) hh = cand_hash(f, se, tk);
+    const int pos = atomicAdd(count, 1);
+    if (pos < kExactCap) {
+        bl_D[pos] = D;
+        bl_h[pos] = hh;
+    }
+}
+
+// Kept iff (D, hash) <= (selD, selH) lexicographically; the hash is computed only on
+// a distance tie.
+__device__ __forceinline__ bool is_selected(const FrameCtx& f, uint64_t selD, uint64_t selH,
+                                            uint64_t D, int se, int32_t tk, uint64_t& hh,
+                                            bool& have_h) {
+    if (D < selD) return true;
+    if (D != selD) return false;
+    hh = cand_hash(f, se, tk);
+    have_h = true;
+    return hh <= selH;
+}
+
+__device__ __forceinline__ void publish_hash(Links* lkn, uint64_t hh, int slot) {
+    uint32_t hs = (uint32_t)hh & (kHashSlots - 1);
+    for (int probe = 0; probe < kHashSlots; ++probe) {
+        if (atomicCAS(&lkn->ht[hs], -1, slot) == -1) break;
+        hs = (hs + 1) & (kHashSlots - 1);
+    }
+}
+
+// Entry `se` keeps its prefix: copy it into `slot` of the next beam with its new masses.
+__device__ __forceinline__ void emit_stay(const FrameCtx& f, BeamSlab* nxt, Links* lkn, int slot,
+                                          int beam, int se, double pb, double pnb, double tot) {
+    if (slot >= beam) return;  // only after a hash collision
+    const BeamSlab* cur = f.cur;
+    const uint64_t hh = cur->h[se];
+    nxt->h[slot] = hh;
+    nxt->hp[slot] = cur->hp[se];
+    nxt->pb[slot] = pb;
+    nxt->pnb[slot] = pnb;
+    nxt->ptot[slot] = tot;
+    nxt->last[slot] = cur->last[se];
+    nxt->node[slot] = cur->node[se];
+    nxt->plen[slot] = cur->plen[se];
+    nxt->xanc[slot] = cur->xanc[se];
+    publish_hash(lkn, hh, slot);
+}
+
+// Entry `se` extended by token `tk` becomes a new prefix in `slot`; its trie node id is
+// fixed by (frame, slot), so no counter is needed.
+__device__ __forceinline__ void emit_ext(const FrameCtx& f, BeamSlab* nxt, Links* lkn, int slot,
+                                         int beam, int t, uint64_t D, int se, int32_t tk,
+                                         uint64_t hh, bool have_h, TrieNode* trie,
+                                         int64_t trie_stride) {
+    if (slot >= beam) return;
+    const BeamSlab* cur = f.cur;
+    if (!have_h) hh = cand_hash(f, se, tk);
+    const double sc = key_value(f.Rk - D);
+    const int node = 1 + t * beam + slot;
+    const int depth = cur->plen[se] + 1;
+    const int32_t xa = cur->xanc[se];
+    nxt->h[slot] = hh;
+    nxt->hp[slot] = cur->h[se];
+    nxt->pb[slot] = -INFINITY;
+    nxt->pnb[slot] = sc;
+    nxt->ptot[slot] = sc;
+    nxt->last[slot] = tk;
+    nxt->node[slot] = node;
+    nxt->plen[slot] = depth;
+    nxt->xanc[slot] = (depth & 7) == 0 ? node : xa;
+    TrieNode tn;
+    tn.parent = cur->node[se];
+    tn.xup = xa;
+    tn.tok = tk;
+    tn.depth = depth;
+    if ((int64_t)node < trie_stride) trie[node] = tn;
+    publish_hash(lkn, hh, slot);
+}
+
+template <int LM>
 __global__ __launch_bounds__(kThreads) void beam_kernel(BeamArgs a) {
     __shared__ BeamSlab slab[2];
-    __shared__ double st_pb[kMaxBeam], st_pnb[kMaxBeam], st_tot[kMaxBeam];
-    __shared__ int32_t par[kMaxBeam], first_kid[kMaxBeam], next_kid[kMaxBeam];
-    __shared__ int32_t ht[kHashSlots];
-    __shared__ uint32_t hist[3][kBins];
+    __shared__ Links links[2];
+    __shared__ uint32_t hfine[kFine];
+    __shared__ uint32_t hcoarse[kCoarse];
     __shared__ uint64_t bl_D[kExactCap], bl_h[kExactCap];
-    __shared__ uint64_t sh_kmax, sh_kmin, sh_selD, sh_selH;
-    __shared__ int32_t sh_nnew, sh_nodes, sh_blcount, sh_best;
+    __shared__ FrameHdr ring[kChunk];
+    __shared__ uint64_t sh_selD, sh_selH, sh_kbest;
+    __shared__ int32_t sh_nnew, sh_blcount, sh_best;
     extern __shared__ __align__(16) unsigned char dyn_lds[];
 
     const int tid = threadIdx.x;
@@ -136,25 +441,50 @@ __global__ __launch_bounds__(kThreads) void beam_kernel(BeamArgs a) {
     const int b = blockIdx.x;
     const int V = a.V;
     const int beam = a.beam;
+    const int64_t trie_stride = a.trie_stride;
 
     float* dense_lp = reinterpret_cast<float*>(dyn_lds);
     uint16_t* s_tok = reinterpret_cast<uint16_t*>(dyn_lds + (size_t)V * sizeof(float));
     float* lm_s = reinterpret_cast<float*>(dyn_lds + lm_lds_offset(V));
-    const bool has_lm = a.lm_table != nullptr;
-    const float* lm = a.lm_in_lds ? lm_s : a.lm_table;
+    constexpr bool has_lm = LM != kLmNone;
 
     int32_t len = a.lengths[b];
     len = len < 0 ? 0 : (len > a.T ? a.T : len);
+    const int64_t g_base = (int64_t)b * a.T;
+    const Survivor* rec_all = a.rec;
+    const int pg_shift = a.pg_shift;
+
+    // ---- header chunks: 32 frames x 64 B = 128 threads x 16 B ------------------------
+    // Chunk c+1 is loaded into registers while chunk c is decoded and moved into LDS at
+    // the chunk boundary, so the only wait for it sits in the outer (per-chunk) loop.
+    const uint4* hdr_words = reinterpret_cast<const uint4*>(a.hdr + g_base);
+#define FLTOP_LOAD_CHUNK(dst, c)                                                         \
+    do {                                                                                 \
+        (dst) = make_uint4(0u, 0u, 0u, 0u);                                              \
+        if (tid < 4 * kChunk && (c) * kChunk + (tid >> 2) < len)                         \
+            (dst) = hdr_words[(int64_t)(c) * (4 * kChunk) + tid];                        \
+    } while (0)
+#define FLTOP_REC_BASE(g, offset) \
+    (rec_all + ((((g) >> pg_shift) << pg_shift) * (int64_t)V) + (offset))
+#define FLTOP_RING_HEAD(t) (*reinterpret_cast<const HdrHead*>(&ring[(t) % kChunk]))
+
+    uint4 staged;
+    FLTOP_LOAD_CHUNK(staged, 0);
 
     // ---- one-time initialisation ------------------------------------------------
     for (int v = tid; v < V; v += kThreads) dense_lp[v] = -INFINITY;
-    for (int i = tid; i < 3 * kBins; i += kThreads) (&hist[0][0])[i] = 0u;
-    if (a.lm_in_lds)
+    for (int i = tid; i < kFine; i += kThreads) hfine[i] = 0u;
+    if (tid < kCoarse) hcoarse[tid] = 0u;
+    if (LM == kLmLds)
         for (int i = tid; i < V * V; i += kThreads) lm_s[i] = a.lm_table[i];
-    if (tid < kMaxBeam) {
-        par[tid] = -1;
-        first_kid[tid] = -1;
-        next_kid[tid] = -1;
+    for (int g2 = 0; g2 < 2; ++g2) {
+        if (tid < kMaxBeam) {
+            links[g2].par[tid] = -1;
+            links[g2].first_kid[tid] = -1;
+            links[g2].next_kid[tid] = -1;
+            links[g2].kidmask[tid] = 0u;
+        }
+        for (int i = tid; i < kHashSlots; i += kThreads) links[g2].ht[i] = -1;
     }
     if (tid == 0) {
         BeamSlab& s0 = slab[0];
@@ -166,444 +496,465 @@ __global__ __launch_bounds__(kThreads) void beam_kernel(BeamArgs a) {
         s0.last[0] = -1;
         s0.node[0] = 0;
         s0.plen[0] = 0;
-        sh_kmax = order_key(0.0);
-        sh_kmin = order_key(0.0);
-        sh_nodes = 1;
+        s0.xanc[0] = 0;
         sh_nnew = 0;
         sh_blcount = 0;
     }
-    TrieNode* trie = a.trie + (int64_t)b * a.trie_stride;
+    TrieNode* trie = a.trie + (int64_t)b * trie_stride;
     const double lm_ub = has_lm ? fmax(0.0, (double)a.lm_bound[0]) : 0.0;
     __syncthreads();
 
-    int cur_i = 0;
+    FrameCtx fc;
+    fc.dense_lp = dense_lp;
+    fc.s_tok = s_tok;
+    fc.lm_lds = (LdsFloatPtr)lm_s;
+    fc.lm_glb = a.lm_table;
+    fc.lm_alpha = a.lm_alpha;
+    fc.lm_beta = a.lm_beta;
+    fc.V = V;
+
+    int gen = 0;         // beam generation: slab[gen], links[gen]
     int n_live = 1;
-    int hist_pass = 0;  // running index of histogram passes: pass p uses hist[p % 3]
+    bool dirty = false;  // entries were updated in place since the last barrier
+    double kmax_v = 0.0, kmin_v = 0.0;  // bounds of the best / worst score in the beam
 
     // statistics kept by thread 0
     uint64_t st_surv = 0, st_cand = 0, st_peak = 0, st_beam = 0, st_pass = 0, st_exact = 0,
              st_drop = 0;
+#ifdef FLTOP_PHASE_CLOCKS
+    uint64_t ph_clk[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    uint64_t ph_last = clock64();
+#endif
 
-    const int64_t g_base = (int64_t)b * a.T;
-    FrameHdr hd_next;
-    hd_next.count = 0;
-    hd_next.offset = 0;
-    hd_next.top = 0.0f;
-    if (len > 0) hd_next = a.hdr[g_base];
+    const int n_chunks = (len + kChunk - 1) / kChunk;
+    for (int c = 0; c < n_chunks; ++c) {
+    // ---- chunk boundary: headers of frames [32c, 32c+32) into LDS, next chunk requested --
+    lds_barrier();  // nobody still reads the previous chunk's headers
+    if (tid < 4 * kChunk) reinterpret_cast<uint4*>(&ring[0])[tid] = staged;
+    lds_barrier();
+    dirty = false;
+    FLTOP_LOAD_CHUNK(staged, c + 1);
+    const int t_end = min(len, (c + 1) * kChunk);
+    HdrHead head_next = FLTOP_RING_HEAD(c * kChunk);  // read one frame ahead inside the chunk
 
-    for (int t = 0; t < len; ++t) {
+    for (int t = c * kChunk; t < t_end; ++t) {
         const int64_t g = g_base + t;
-        const FrameHdr hd = hd_next;
-        if (t + 1 < len) hd_next = a.hdr[g + 1];
+        const HdrHead hd = head_next;
         const int K = hd.count;
-        const Survivor* recs = a.rec + (g / a.fpb) * (int64_t)a.fpb * V + hd.offset;
+        if (t + 1 < t_end) head_next = FLTOP_RING_HEAD(t + 1);
+        if (tid == 0) st_surv += (uint64_t)K;
+        if (n_live == 0) continue;
 
-        // ---- stage the frame's survivors -------------------------------------
-        for (int k = tid; k < K; k += kThreads) {
-            const Survivor s = recs[k];
-            s_tok[k] = (uint16_t)s.tok;
-            dense_lp[s.tok] = s.lp;
-        }
-        __syncthreads();
+        BeamSlab* const cur = &slab[gen];
+        BeamSlab* const nxt = &slab[gen ^ 1];
+        Links* const lk = &links[gen];
+        Links* const lkn = &links[gen ^ 1];
 
-        if (n_live > 0) {
-            BeamSlab& cur = slab[cur_i];
-            BeamSlab& nxt = slab[cur_i ^ 1];
-            const int nb0 = (K > 0 && s_tok[0] == 0) ? 1 : 0;  // records ascend: blank first
-            const int Knb = K - nb0;
-            const double lp_blank = (double)dense_lp[0];
-
-            auto lm_term = [&](int32_t prev, int32_t tok) -> double {
-                if (!has_lm) return 0.0;
-                const int32_t row = prev < 0 ? 0 : prev;
-                return a.lm_alpha * (double)lm[(int64_t)row * V + tok] + a.lm_beta;
-            };
-
-            // ---- stay candidates: entry j keeps its prefix ---------------------
+        // ---- blank-only frame: no prefix changes, order is preserved -------------------
+        if (K == 1 && hd.s0.tok == 0 && hd.s0.lp > -INFINITY) {
+            const double x = (double)hd.s0.lp;
             if (tid < n_live) {
-                const int j = tid;
-                const int32_t lj = cur.last[j];
-                const double lpl = (lj >= 0) ? (double)dense_lp[lj] : -INFINITY;
-                const double pb2 = cur.ptot[j] + lp_blank;
-                const double a1 = cur.pnb[j] + lpl;
-                double a2 = -INFINITY;
-                const int p = par[j];
-                if (p >= 0 && lpl > -INFINITY) {
-                    const int32_t lpar = cur.last[p];
-                    const double src = (lpar == lj) ? cur.pb[p] : cur.ptot[p];
-                    a2 = src + lpl + lm_term(lpar, lj);
-                }
-                const double pnb2 = lse2(a1, a2);
-                st_pb[j] = pb2;
-                st_pnb[j] = pnb2;
-                st_tot[j] = lse2(pb2, pnb2);
+                const double nt = cur->ptot[tid] + x;
+                cur->pb[tid] = nt;
+                cur->pnb[tid] = -INFINITY;
+                cur->ptot[tid] = nt;
             }
-            __syncthreads();
+            kmax_v += x;
+            kmin_v += x;
+            dirty = true;
+            if (tid == 0) {
+                st_cand += (uint64_t)n_live;
+                if ((uint64_t)n_live > st_peak) st_peak = (uint64_t)n_live;
+                st_beam += (uint64_t)n_live;
+            }
+            PHASE_MARK(7);
+            continue;
+        }
 
-            // virtual candidate c: [0, n_live) stay, then n_live*Knb extensions
-            const int n_virtual = n_live + n_live * Knb;
-            auto cand_score = [&](int c, int& src_entry, int32_t& tok) -> double {
-                if (c < n_live) {
-                    src_entry = c;
-                    tok = -1;
-                    return st_tot[c];
+        // ---- survivors: registers for K <= 6, LDS staging beyond ------------------------
+        const bool big = K > kRegK;
+        fc.cur = cur;
+        fc.lk = lk;
+        fc.big = big;
+        fc.t0 = K > 0 ? hd.s0.tok : -1;
+        fc.t1 = K > 1 ? hd.s1.tok : -1;
+        fc.l0 = hd.s0.lp;
+        fc.l1 = hd.s1.lp;
+        fc.t2 = fc.t3 = fc.t4 = fc.t5 = -1;
+        fc.l2 = fc.l3 = fc.l4 = fc.l5 = -INFINITY;
+        if (!big && K > 2) {
+            const FrameHdr* full = &ring[t % kChunk];
+            const Survivor f2 = full->first[2], f3 = full->first[3], f4 = full->first[4],
+                           f5 = full->first[5];
+            fc.t2 = f2.tok;
+            fc.l2 = f2.lp;
+            if (K > 3) {
+                fc.t3 = f3.tok;
+                fc.l3 = f3.lp;
+            }
+            if (K > 4) {
+                fc.t4 = f4.tok;
+                fc.l4 = f4.lp;
+            }
+            if (K > 5) {
+                fc.t5 = f5.tok;
+                fc.l5 = f5.lp;
+            }
+        }
+        if (tid == 0) {
+            sh_nnew = 0;
+            sh_blcount = 0;
+        }
+        if (big) {
+            const Survivor* recs = FLTOP_REC_BASE(g, hd.offset);
+            for (int k = tid; k < K; k += kThreads) {
+                const Survivor s = recs[k];
+                s_tok[k] = (uint16_t)s.tok;
+                dense_lp[s.tok] = s.lp;
+            }
+        }
+        if (big || dirty) {
+            lds_barrier();
+            dirty = false;
+        }
+
+        fc.nb0 = (K > 0 && surv_tok(fc, 0) == 0) ? 1 : 0;  // records ascend: blank first
+        fc.Knb = K - fc.nb0;
+        fc.div_magic = fc.Knb > 1 ? (uint32_t)(0x100000000ull / (uint32_t)fc.Knb) + 1u : 0u;
+        const double lp_blank = lp_of(fc, 0);
+        const int n_ext = n_live * fc.Knb;
+        const int M = (n_ext + kThreads - 1) / kThreads;  // extension candidates per thread
+        const int e_first = (tid + kThreads / 2) & (kThreads - 1);  // waves 2,3 take them first
+
+        // upper bound of every candidate score -> reference key
+        const double ref = kmax_v + (double)hd.top + lm_ub + 1.0986122886681098 + 1e-3;
+        fc.Rk = order_key(ref);
+        const uint64_t Rk = fc.Rk;
+
+        // ---- candidates owned by this thread ----------------------------------------
+        // two cached extension candidates (e_first, e_first + 256) ...
+        uint64_t cD0 = kAllOnes, cD1 = kAllOnes;  // ~0 marks "no live candidate"
+        int cI0 = 0, cI1 = 0;
+        int32_t cT0 = 0, cT1 = 0;
+        if (e_first < n_ext) cD0 = eval_ext<LM>(fc, e_first, cI0, cT0);
+        if (e_first + kThreads < n_ext) cD1 = eval_ext<LM>(fc, e_first + kThreads, cI1, cT1);
+        // ... and the stay candidate of entry `tid`
+        double my_pb = -INFINITY, my_pnb = -INFINITY, my_tot = -INFINITY;
+        uint64_t D_stay = kAllOnes;
+        if (tid < n_live) {
+            const int j = tid;
+            const int32_t lj = cur->last[j];
+            const double lpl = lp_of(fc, lj);
+            my_pb = cur->ptot[j] + lp_blank;
+            const double a1 = cur->pnb[j] + lpl;
+            double a2 = -INFINITY;
+            const int p = lk->par[j];
+            if (p >= 0 && lpl > -INFINITY) {
+                const int32_t lpar = cur->last[p];
+                const double src = (lpar == lj) ? cur->pb[p] : cur->ptot[p];
+                a2 = src + lpl + lm_term<LM>(fc, lpar, lj);
+            }
+            my_pnb = lse2(a1, a2);
+            my_tot = lse2(my_pb, my_pnb);
+            if (my_tot > -INFINITY) D_stay = Rk - order_key(my_tot);
+        }
+        PHASE_MARK(1);
+
+        // ---- selection: find (selD, selH); keep D < selD or (D == selD and hash <= selH)
+        uint64_t selD = kAllOnes, selH = kAllOnes;
+        uint64_t kbest_key = 0;  // upper bound of the best candidate's key
+        {
+            // initial bucket width from the spread of the current beam
+            const double est_low = kmin_v + (double)hd.top - 2.0;
+            uint64_t Dest = Rk - order_key(est_low);
+            if (Dest < 1024) Dest = 1024;
+            Window w;
+            w.sh = 64 - __clzll((long long)Dest) - 10;
+            if (w.sh < 0) w.sh = 0;
+            if (w.sh > kMaxShift) w.sh = kMaxShift;
+            w.lo = 0;
+            w.mode = 0;
+            w.Dfix = 0;
+            int need = beam;
+            for (int iter = 0; iter < 40; ++iter) {
+                if (iter > 0) {  // rare: the single histogram is reused for a refined window
+                    lds_barrier();
+                    for (int i = tid; i < kFine; i += kThreads) hfine[i] = 0u;
+                    if (tid < kCoarse) hcoarse[tid] = 0u;
+                    lds_barrier();
                 }
-                const int e = c - n_live;
-                const int i = e / Knb;
-                const int k = e - i * Knb;
-                const int32_t s = s_tok[nb0 + k];
-                src_entry = i;
-                tok = s;
-                const int32_t li = cur.last[i];
-                int guard = 0;
-                for (int kid = first_kid[i]; kid >= 0 && guard < kMaxBeam; kid = next_kid[kid], ++guard)
-                    if (cur.last[kid] == s) return -INFINITY;  // merged into that beam entry
-                const double src = (s == li) ? cur.pb[i] : cur.ptot[i];
-                return src + (double)dense_lp[s] + lm_term(li, s);
-            };
-            auto cand_hash = [&](int src_entry, int32_t tok) -> uint64_t {
-                return tok < 0 ? cur.h[src_entry] : child_hash(cur.h[src_entry], tok);
-            };
+                if (D_stay != kAllOnes) hist_add(fc, w, D_stay, tid, -1, hfine, hcoarse);
+                if (cD0 != kAllOnes) hist_add(fc, w, cD0, cI0, cT0, hfine, hcoarse);
+                if (cD1 != kAllOnes) hist_add(fc, w, cD1, cI1, cT1, hfine, hcoarse);
+                for (int m = kRegCand; m < M; ++m) {
+                    const int e = e_first + m * kThreads;
+                    if (e >= n_ext) break;
+                    int se;
+                    int32_t tk;
+                    const uint64_t D = eval_ext<LM>(fc, e, se, tk);
+                    if (D != kAllOnes) hist_add(fc, w, D, se, tk, hfine, hcoarse);
+                }
+                lds_barrier();
+                PHASE_MARK(2);
+                // every wave scans the histogram redundantly (results are uniform)
+                const int cs = (int)hcoarse[lane];
+                const int incl = wave_inclusive_scan(cs);
+                const int total = __builtin_amdgcn_readlane(incl, kWave - 1);
+                if (iter == 0) {
+                    if (tid == 0) {
+                        st_cand += (uint64_t)total;
+                        if ((uint64_t)total > st_peak) st_peak = (uint64_t)total;
+                    }
+                    // first occupied bin -> bound of the best candidate (window starts at 0)
+                    const uint64_t occ = __ballot(cs > 0);
+                    if (occ != 0) {
+                        const int lmin = __ffsll((long long)occ) - 1;
+                        const uint32_t f = hfine[lmin * 16 + (lane & 15)];
+                        const uint64_t occf = __ballot(f > 0 && lane < 16);
+                        const int bmin = lmin * 16 + (__ffsll((long long)occf) - 1);
+                        const uint64_t dmin = (w.sh > 0 && ((uint64_t)bmin >> (64 - w.sh)) != 0)
+                                                  ? kAllOnes
+                                                  : ((uint64_t)bmin << w.sh);
+                        kbest_key = dmin > Rk ? 0 : Rk - dmin;
+                    }
+                }
+                if (tid == 0) st_pass++;
+                if (total <= need) {  // everything left in the window is kept
+                    selD = (w.mode == 0) ? kAllOnes : w.Dfix;
+                    selH = kAllOnes;
+                    break;
+                }
+                // coarse bin holding the need-th candidate, then the fine bin inside it
+                const uint64_t cross = __ballot(incl >= need);
+                const int lstar = __ffsll((long long)cross) - 1;
+                const int above_c =
+                    __builtin_amdgcn_readlane(incl, lstar) - __builtin_amdgcn_readlane(cs, lstar);
+                const int fs = (int)hfine[lstar * 16 + (lane & 15)];
+                const int fincl = row_inclusive_scan(fs);
+                const uint64_t fcross = __ballot(lane < 16 && above_c + fincl >= need);
+                const int fl = __ffsll((long long)fcross) - 1;
+                const int bstar = lstar * 16 + fl;
+                const int n_b = __builtin_amdgcn_readlane(fs, fl);
+                const int n_above = above_c + __builtin_amdgcn_readlane(fincl, fl) - n_b;
+                const int r = need - n_above;  // 1 <= r <= n_b
+                const bool clamp_bin = (bstar == kFine - 1) && (w.sh < kMaxShift);
 
-            // upper bound of every candidate score -> reference key
-            const double ref = key_value(sh_kmax) + (double)hd.top + lm_ub + 1.0986122886681098 + 1e-3;
-            const uint64_t Rk = order_key(ref);
-
-            // ---- selection: find (selD, selH); keep D < selD or (D == selD and hash <= selH)
-            uint64_t selD = kAllOnes, selH = kAllOnes;
-            {
-                // initial bucket width from the spread of the current beam
-                const double est_low = key_value(sh_kmin) + (double)hd.top - 2.0;
-                uint64_t Dest = Rk - order_key(est_low);
-                if (Dest < 1024) Dest = 1024;
-                int sh = 64 - __clzll((long long)Dest) - 10;
-                if (sh < 0) sh = 0;
-                if (sh > kMaxShift) sh = kMaxShift;
-                uint64_t lo = 0;
-                int need = beam;
-                int mode = 0;  // 0: window over score distance, 1: window over hash at D == Dfix
-                uint64_t Dfix = 0;
-                bool first = true;
-                for (int iter = 0; iter < 40; ++iter) {
-                    uint32_t* H = hist[hist_pass % 3];
-                    uint32_t* Hz = hist[(hist_pass + 1) % 3];
-                    ++hist_pass;
-                    for (int i = tid; i < kBins; i += kThreads) Hz[i] = 0u;
-                    for (int c = tid; c < n_virtual; c += kThreads) {
+                if (n_b == r) {  // the boundary bucket is taken whole
+                    const uint64_t top = clamp_bin ? kAllOnes : bucket_top(w.lo, bstar, w.sh);
+                    if (w.mode == 0) {
+                        selD = top;
+                        selH = kAllOnes;
+                    } else {
+                        selD = w.Dfix;
+                        selH = top;
+                    }
+                    break;
+                }
+                if (n_b <= kExactCap) {
+                    // ---- exact ranking of the boundary bucket by (distance, hash)
+                    if (tid == 0) st_exact++;
+                    if (D_stay != kAllOnes)
+                        boundary_add(fc, w, bstar, D_stay, tid, -1, &sh_blcount, bl_D, bl_h);
+                    if (cD0 != kAllOnes)
+                        boundary_add(fc, w, bstar, cD0, cI0, cT0, &sh_blcount, bl_D, bl_h);
+                    if (cD1 != kAllOnes)
+                        boundary_add(fc, w, bstar, cD1, cI1, cT1, &sh_blcount, bl_D, bl_h);
+                    for (int m = kRegCand; m < M; ++m) {
+                        const int e = e_first + m * kThreads;
+                        if (e >= n_ext) break;
                         int se;
                         int32_t tk;
-                        const double sc = cand_score(c, se, tk);
-                        if (!(sc > -INFINITY)) continue;
-                        const uint64_t D = Rk - order_key(sc);
-                        uint64_t x;
-                        if (mode == 0) {
-                            x = D;
-                        } else {
-                            if (D != Dfix) continue;
-                            x = cand_hash(se, tk);
+                        const uint64_t D = eval_ext<LM>(fc, e, se, tk);
+                        if (D != kAllOnes)
+                            boundary_add(fc, w, bstar, D, se, tk, &sh_blcount, bl_D, bl_h);
+                    }
+                    lds_barrier();
+                    if (tid < kWave) {
+                        const int n = min(sh_blcount, kExactCap);
+                        const bool mine = lane < n;
+                        const uint64_t myD = mine ? bl_D[lane] : 0;
+                        const uint64_t myH = mine ? bl_h[lane] : 0;
+                        int rank = 0, same = 0;
+                        for (int e = 0; e < n; ++e) {
+                            const uint64_t oD = bl_D[e], oH = bl_h[e];
+                            rank += (oD < myD || (oD == myD && oH < myH)) ? 1 : 0;
+                            same += (oD == myD && oH == myH) ? 1 : 0;
                         }
-                        if (x < lo) continue;
-                        uint64_t q = (x - lo) >> sh;
-                        const int bin = q > (uint64_t)(kBins - 1) ? (kBins - 1) : (int)q;
-                        atomicAdd(&H[bin_slot(bin)], 1u);
-                    }
-                    __syncthreads();
-                    // every wave scans the histogram redundantly (results are uniform)
-                    uint32_t v[kBinsPerLane];
-                    uint32_t s = 0;
-#pragma unroll
-                    for (int q = 0; q < kBinsPerLane; ++q) {
-                        v[q] = H[q * kWave + lane];
-                        s += v[q];
-                    }
-                    uint32_t incl = s;
-#pragma unroll
-                    for (int o = 1; o < kWave; o <<= 1) {
-                        const uint32_t up = __shfl_up(incl, o, kWave);
-                        if (lane >= o) incl += up;
-                    }
-                    const uint32_t excl = incl - s;
-                    const int total = (int)__shfl(incl, kWave - 1, kWave);
-                    if (first) {
-                        first = false;
-                        if (tid == 0) {
-                            st_cand += (uint64_t)total;
-                            if ((uint64_t)total > st_peak) st_peak = (uint64_t)total;
+                        // the r-th best member (members that collide in both fields tie)
+                        if (mine && rank <= r - 1 && r - 1 < rank + same) {
+                            sh_selD = myD;
+                            sh_selH = myH;
                         }
                     }
-                    if (tid == 0) st_pass++;
-                    if (total <= need) {  // everything left in the window is kept
-                        if (mode == 0) {
-                            selD = kAllOnes;
-                            selH = kAllOnes;
-                        } else {
-                            selD = Dfix;
-                            selH = kAllOnes;
-                        }
-                        break;
-                    }
-                    const bool here = (excl < (uint32_t)need) && ((uint32_t)need <= incl);
-                    const uint64_t hm = __ballot(here);
-                    const int src_lane = __ffsll((long long)hm) - 1;
-                    int bstar = 0, n_above = 0, n_b = 0;
-                    if (here) {
-                        uint32_t cum = excl;
-#pragma unroll
-                        for (int q = 0; q < kBinsPerLane; ++q) {
-                            if (n_b == 0 && cum + v[q] >= (uint32_t)need) {
-                                bstar = lane * kBinsPerLane + q;
-                                n_above = (int)cum;
-                                n_b = (int)v[q];
-                            }
-                            cum += v[q];
-                        }
-                    }
-                    bstar = __shfl(bstar, src_lane, kWave);
-                    n_above = __shfl(n_above, src_lane, kWave);
-                    n_b = __shfl(n_b, src_lane, kWave);
-                    const int r = need - n_above;  // 1 <= r <= n_b
-                    const bool clamp_bin = (bstar == kBins - 1) && (sh < kMaxShift);
-
-                    if (n_b == r) {  // the boundary bucket is taken whole
-                        const uint64_t top = clamp_bin ? kAllOnes : bucket_top(lo, bstar, sh);
-                        if (mode == 0) {
-                            selD = top;
-                            selH = kAllOnes;
-                        } else {
-                            selD = Dfix;
-                            selH = top;
-                        }
-                        break;
-                    }
-                    if (n_b <= kExactCap) {
-                        // ---- exact ranking of the boundary bucket by (distance, hash)
-                        if (tid == 0) st_exact++;
-                        for (int c = tid; c < n_virtual; c += kThreads) {
-                            int se;
-                            int32_t tk;
-                            const double sc = cand_score(c, se, tk);
-                            if (!(sc > -INFINITY)) continue;
-                            const uint64_t D = Rk - order_key(sc);
-                            uint64_t x;
-                            uint64_t hh = 0;
-                            bool have_h = false;
-                            if (mode == 0) {
-                                x = D;
-                            } else {
-                                if (D != Dfix) continue;
-                                hh = cand_hash(se, tk);
-                                have_h = true;
-                                x = hh;
-                            }
-                            if (x < lo) continue;
-                            uint64_t q = (x - lo) >> sh;
-                            const int bin = q > (uint64_t)(kBins - 1) ? (kBins - 1) : (int)q;
-                            if (bin != bstar) continue;
-                            if (!have_h) hh = cand_hash(se, tk);
-                            const int pos = atomicAdd(&sh_blcount, 1);
-                            if (pos < kExactCap) {
-                                bl_D[pos] = D;
-                                bl_h[pos] = hh;
-                            }
-                        }
-                        __syncthreads();
-                        if (tid < kWave) {
-                            const int n = min(sh_blcount, kExactCap);
-                            const bool mine = lane < n;
-                            const uint64_t myD = mine ? bl_D[lane] : 0;
-                            const uint64_t myH = mine ? bl_h[lane] : 0;
-                            int rank = 0, same = 0;
-                            for (int e = 0; e < n; ++e) {
-                                const uint64_t oD = bl_D[e], oH = bl_h[e];
-                                rank += (oD < myD || (oD == myD && oH < myH)) ? 1 : 0;
-                                same += (oD == myD && oH == myH) ? 1 : 0;
-                            }
-                            // the r-th best member (members that collide in both fields tie)
-                            if (mine && rank <= r - 1 && r - 1 < rank + same) {
-                                sh_selD = myD;
-                                sh_selH = myH;
-                            }
-                        }
-                        __syncthreads();
-                        selD = sh_selD;
-                        selH = sh_selH;
-                        if (tid == 0) sh_blcount = 0;
-                        break;
-                    }
-                    // ---- boundary bucket too large: narrow (or widen) the window
-                    need = r;
-                    if (clamp_bin) {
-                        lo = sat_add(lo, (uint64_t)(kBins - 1) << sh);
-                        sh = min(kMaxShift, sh + 8);
-                    } else if (sh > 0) {
-                        lo = sat_add(lo, (uint64_t)bstar << sh);
-                        sh = max(0, sh - 10);
-                    } else if (mode == 0) {
-                        // more than kExactCap candidates share one score: order them by hash
-                        Dfix = lo + (uint64_t)bstar;
-                        mode = 1;
-                        lo = 0;
-                        sh = kMaxShift;
-                    } else {
-                        // identical score and identical hash (collision): keep them all
-                        selD = Dfix;
-                        selH = lo + (uint64_t)bstar;
-                        break;
-                    }
+                    lds_barrier();
+                    selD = sh_selD;
+                    selH = sh_selH;
+                    PHASE_MARK(4);
+                    break;
                 }
-            }
-
-            // ---- compaction: selected candidates become the next beam ------------
-            for (int c0 = 0; c0 < n_virtual; c0 += kThreads) {
-                const int c = c0 + tid;
-                bool sel = false;
-                int se = 0;
-                int32_t tk = -1;
-                double sc = -INFINITY;
-                uint64_t hh = 0;
-                bool have_h = false;
-                if (c < n_virtual) {
-                    sc = cand_score(c, se, tk);
-                    if (sc > -INFINITY) {
-                        const uint64_t D = Rk - order_key(sc);
-                        if (D < selD) {
-                            sel = true;
-                        } else if (D == selD) {
-                            hh = cand_hash(se, tk);
-                            have_h = true;
-                            sel = hh <= selH;
-                        }
-                    }
-                }
-                const uint64_t m_sel = __ballot(sel);
-                const uint64_t m_ext = __ballot(sel && tk >= 0);
-                if (m_sel == 0) continue;
-                int slot_base = 0, node_base = 0;
-                const int leader = __ffsll((long long)m_sel) - 1;
-                if (lane == leader) {
-                    slot_base = atomicAdd(&sh_nnew, __popcll(m_sel));
-                    if (m_ext) node_base = atomicAdd(&sh_nodes, __popcll(m_ext));
-                }
-                slot_base = __shfl(slot_base, leader, kWave);
-                node_base = __shfl(node_base, leader, kWave);
-                if (!sel) continue;
-                const int slot = slot_base + lanes_below(m_sel, lane);
-                if (slot >= beam) continue;  // only after a hash collision; counted below
-                if (tk < 0) {
-                    nxt.h[slot] = cur.h[se];
-                    nxt.hp[slot] = cur.hp[se];
-                    nxt.pb[slot] = st_pb[se];
-                    nxt.pnb[slot] = st_pnb[se];
-                    nxt.ptot[slot] = sc;
-                    nxt.last[slot] = cur.last[se];
-                    nxt.node[slot] = cur.node[se];
-                    nxt.plen[slot] = cur.plen[se];
+                // ---- boundary bucket too large: narrow (or widen) the window
+                need = r;
+                if (clamp_bin) {
+                    w.lo = sat_add(w.lo, (uint64_t)(kFine - 1) << w.sh);
+                    w.sh = min(kMaxShift, w.sh + 8);
+                } else if (w.sh > 0) {
+                    w.lo = sat_add(w.lo, (uint64_t)bstar << w.sh);
+                    w.sh = max(0, w.sh - 10);
+                } else if (w.mode == 0) {
+                    // more than kExactCap candidates share one score: order them by hash
+                    w.Dfix = w.lo + (uint64_t)bstar;
+                    w.mode = 1;
+                    w.lo = 0;
+                    w.sh = kMaxShift;
                 } else {
-                    if (!have_h) hh = cand_hash(se, tk);
-                    const int node = node_base + lanes_below(m_ext, lane);
-                    nxt.h[slot] = hh;
-                    nxt.hp[slot] = cur.h[se];
-                    nxt.pb[slot] = -INFINITY;
-                    nxt.pnb[slot] = sc;
-                    nxt.ptot[slot] = sc;
-                    nxt.last[slot] = tk;
-                    nxt.node[slot] = node;
-                    nxt.plen[slot] = cur.plen[se] + 1;
-                    TrieNode tn;
-                    tn.parent = cur.node[se];
-                    tn.tok = tk;
-                    if ((int64_t)node < a.trie_stride) trie[node] = tn;
+                    // identical score and identical hash (collision): keep them all
+                    selD = w.Dfix;
+                    selH = w.lo + (uint64_t)bstar;
+                    break;
                 }
             }
-            __syncthreads();
-
-            // ---- adopt the new beam; rebuild parent links ------------------------
-            int n_new = sh_nnew;
-            if (n_new > beam) {
-                if (tid == 0) st_drop += (uint64_t)(n_new - beam);
-                n_new = beam;
-            }
-            if (tid == 0) st_beam += (uint64_t)n_new;
-            for (int i = tid; i < kHashSlots; i += kThreads) ht[i] = -1;
-            if (tid < kMaxBeam) first_kid[tid] = -1;
-            __syncthreads();
-            if (tid == 0) {
-                sh_nnew = 0;
-                sh_kmax = 0;
-                sh_kmin = kAllOnes;
-            }
-            if (tid < n_new) {
-                uint32_t slot = (uint32_t)nxt.h[tid] & (kHashSlots - 1);
-                for (int probe = 0; probe < kHashSlots; ++probe) {
-                    if (atomicCAS(&ht[slot], -1, tid) == -1) break;
-                    slot = (slot + 1) & (kHashSlots - 1);
-                }
-            }
-            __syncthreads();
-            if (tid < n_new) {
-                int p = -1;
-                if (nxt.plen[tid] > 0) {
-                    const uint64_t want = nxt.hp[tid];
-                    uint32_t slot = (uint32_t)want & (kHashSlots - 1);
-                    for (int probe = 0; probe < kHashSlots; ++probe) {
-                        const int v = ht[slot];
-                        if (v < 0) break;
-                        if (nxt.h[v] == want) {
-                            p = v;
-                            break;
-                        }
-                        slot = (slot + 1) & (kHashSlots - 1);
-                    }
-                }
-                par[tid] = p;
-                if (p >= 0) next_kid[tid] = atomicExch(&first_kid[p], tid);
-                const uint64_t k = order_key(nxt.ptot[tid]);
-                atomicMax((unsigned long long*)&sh_kmax, (unsigned long long)k);
-                atomicMin((unsigned long long*)&sh_kmin, (unsigned long long)k);
-            }
-            n_live = n_new;
-            cur_i ^= 1;
         }
+        PHASE_MARK(3);
 
-        // un-stage the frame's survivors (every read of dense_lp is behind a barrier above
-        // or, when the beam is dead, there were none)
-        for (int k = tid; k < K; k += kThreads) dense_lp[s_tok[k]] = -INFINITY;
-        if (tid == 0) st_surv += (uint64_t)K;
-        __syncthreads();
-    }
+        // ---- compaction: selected candidates become the next beam ------------------
+        {
+            // the stay candidate and the cached extensions share one slot allocation per wave
+            uint64_t hh0 = 0, hh1 = 0, hhs = 0;
+            bool hv0 = false, hv1 = false, hvs = false;
+            const bool sel_s =
+                D_stay != kAllOnes && is_selected(fc, selD, selH, D_stay, tid, -1, hhs, hvs);
+            const bool sel_0 =
+                cD0 != kAllOnes && is_selected(fc, selD, selH, cD0, cI0, cT0, hh0, hv0);
+            const bool sel_1 =
+                cD1 != kAllOnes && is_selected(fc, selD, selH, cD1, cI1, cT1, hh1, hv1);
+            const int cnt = (sel_s ? 1 : 0) + (sel_0 ? 1 : 0) + (sel_1 ? 1 : 0);
+            const int incl = wave_inclusive_scan(cnt);
+            const int wave_total = __builtin_amdgcn_readlane(incl, kWave - 1);
+            int base = 0;
+            if (wave_total > 0) {
+                if (lane == 0) base = atomicAdd(&sh_nnew, wave_total);
+                base = __builtin_amdgcn_readfirstlane(base);
+            }
+            int slot = base + incl - cnt;
+            if (sel_s) emit_stay(fc, nxt, lkn, slot++, beam, tid, my_pb, my_pnb, my_tot);
+            if (sel_0)
+                emit_ext(fc, nxt, lkn, slot++, beam, t, cD0, cI0, cT0, hh0, hv0, trie, trie_stride);
+            if (sel_1)
+                emit_ext(fc, nxt, lkn, slot++, beam, t, cD1, cI1, cT1, hh1, hv1, trie, trie_stride);
+        }
+        for (int m = kRegCand; m < M; ++m) {  // candidates beyond the register cache
+            const int e = e_first + m * kThreads;
+            bool sel = false;
+            int se = 0;
+            int32_t tk = 0;
+            uint64_t D = kAllOnes, hh = 0;
+            bool have_h = false;
+            if (e < n_ext) {
+                D = eval_ext<LM>(fc, e, se, tk);
+                if (D != kAllOnes) sel = is_selected(fc, selD, selH, D, se, tk, hh, have_h);
+            }
+            const uint64_t m_sel = __ballot(sel);
+            if (m_sel == 0) continue;
+            int base = 0;
+            if (lane == 0) base = atomicAdd(&sh_nnew, __popcll(m_sel));
+            base = __builtin_amdgcn_readfirstlane(base);
+            if (sel)
+                emit_ext(fc, nxt, lkn, base + lanes_below(m_sel, lane), beam, t, D, se, tk, hh,
+                         have_h, trie, trie_stride);
+        }
+        lds_barrier();
+        PHASE_MARK(5);
+
+        // ---- adopt the new beam; rebuild parent / children links ---------------------
+        int n_new = sh_nnew;
+        if (n_new > beam) {
+            if (tid == 0) st_drop += (uint64_t)(n_new - beam);
+            n_new = beam;
+        }
+        if (tid == 0) st_beam += (uint64_t)n_new;
+        if (tid < n_new) {
+            int p = -1;
+            if (nxt->plen[tid] > 0) {
+                const uint64_t want = nxt->hp[tid];
+                uint32_t hs = (uint32_t)want & (kHashSlots - 1);
+                for (int probe = 0; probe < kHashSlots; ++probe) {
+                    const int v = lkn->ht[hs];
+                    if (v < 0) break;
+                    if (nxt->h[v] == want) {
+                        p = v;
+                        break;
+                    }
+                    hs = (hs + 1) & (kHashSlots - 1);
+                }
+            }
+            lkn->par[tid] = p;
+            if (p >= 0) {
+                lkn->next_kid[tid] = atomicExch(&lkn->first_kid[p], tid);
+                atomicOr(&lkn->kidmask[p], 1u << (nxt->last[tid] & 31));
+            }
+        }
+        // housekeeping behind this frame's last readers: the old generation's links
+        // (next used as the new generation of the following frame), the histogram, and
+        // the staged survivors
+        for (int i = tid; i < kHashSlots; i += kThreads) lk->ht[i] = -1;
+        if (tid < kMaxBeam) {
+            lk->first_kid[tid] = -1;
+            lk->kidmask[tid] = 0u;
+        }
+        for (int i = tid; i < kFine; i += kThreads) hfine[i] = 0u;
+        if (tid < kCoarse) hcoarse[tid] = 0u;
+        if (big)
+            for (int k = tid; k < K; k += kThreads) dense_lp[s_tok[k]] = -INFINITY;
+        if (n_new > 0) {
+            kmax_v = key_value(kbest_key);
+            // worst kept score: the selection threshold when there was one
+            kmin_v = (selD != kAllOnes && selD <= Rk) ? key_value(Rk - selD)
+                                                      : kmin_v + (double)hd.top - 4.0;
+            if (!(kmin_v <= kmax_v)) kmin_v = kmax_v;
+        }
+        n_live = n_new;
+        gen ^= 1;
+        lds_barrier();
+        PHASE_MARK(6);
+    }  // frames of the chunk
+    }  // chunks
+#undef FLTOP_LOAD_CHUNK
+#undef FLTOP_REC_BASE
+#undef FLTOP_RING_HEAD
+
+    // every trie store must have landed before the back-walk reads the nodes
+    __threadfence_block();
+    __syncthreads();
 
     // ---- best prefix (paper: GetHighestScorePrefix) ----------------------------------
-    BeamSlab& fin = slab[cur_i];
+    BeamSlab& fin = slab[gen];
+    int32_t* wp_node = reinterpret_cast<int32_t*>(hfine);  // the histogram is idle now
+    int32_t* wp_depth = wp_node + kWaypoints;
+    static_assert(2 * kWaypoints <= kFine, "way-points alias the histogram");
     if (tid == 0) {
-        sh_kmax = 0;
+        sh_kbest = 0;
         sh_selH = kAllOnes;
         sh_best = -1;
     }
     __syncthreads();
-    if (tid < n_live) atomicMax((unsigned long long*)&sh_kmax, (unsigned long long)order_key(fin.ptot[tid]));
+    if (tid < n_live)
+        atomicMax((unsigned long long*)&sh_kbest, (unsigned long long)order_key(fin.ptot[tid]));
     __syncthreads();
-    if (tid < n_live && order_key(fin.ptot[tid]) == sh_kmax)
+    if (tid < n_live && order_key(fin.ptot[tid]) == sh_kbest)
         atomicMin((unsigned long long*)&sh_selH, (unsigned long long)fin.h[tid]);
     __syncthreads();
-    if (tid < n_live && order_key(fin.ptot[tid]) == sh_kmax && fin.h[tid] == sh_selH) sh_best = tid;
+    if (tid < n_live && order_key(fin.ptot[tid]) == sh_kbest && fin.h[tid] == sh_selH)
+        sh_best = tid;
     __syncthreads();
 
+    const int best = sh_best;
     if (tid == 0) {
-        const int best = sh_best;
         if (best < 0) {
             a.out_lengths[b] = 0;
             a.out_scores[b] = -INFINITY;
         } else {
-            const int n = fin.plen[best];
-            a.out_lengths[b] = n;
+            a.out_lengths[b] = fin.plen[best];
             a.out_scores[b] = (float)fin.ptot[best];
-            int node = fin.node[best];
-            int32_t* dst = a.out_tokens + (int64_t)b * a.T;
-            for (int p = n - 1; p >= 0 && node > 0 && (int64_t)node < a.trie_stride; --p) {
-                const TrieNode tn = trie[node];
-                dst[p] = tn.tok;
-                node = tn.parent;
-            }
         }
         if (a.stats) {
             atomicAdd((unsigned long long*)&a.stats->frames, (unsigned long long)len);
@@ -614,6 +965,52 @@ __global__ __launch_bounds__(kThreads) void beam_kernel(BeamArgs a) {
             atomicAdd((unsigned long long*)&a.stats->select_passes, (unsigned long long)st_pass);
             atomicAdd((unsigned long long*)&a.stats->exact_rankings, (unsigned long long)st_exact);
             atomicAdd((unsigned long long*)&a.stats->overflow_drops, (unsigned long long)st_drop);
+#ifdef FLTOP_PHASE_CLOCKS
+            for (int i = 0; i < 8; ++i)
+                atomicAdd((unsigned long long*)&a.stats->phase_clocks[i],
+                          (unsigned long long)ph_clk[i]);
+#endif
+        }
+    }
+    // Back-walk: thread 0 follows the every-8th-level links and records way-points; then
+    // one thread per way-point walks the (at most 8) parents down to the next way-point.
+    if (best >= 0) {
+        int node = fin.node[best];
+        int depth = fin.plen[best];
+        int32_t* dst = a.out_tokens + (int64_t)b * a.T;
+        while (depth > 0) {  // uniform: node/depth are re-read from LDS after each batch
+            if (tid == 0) {
+                int n = 0;
+                int nd = node, dp = depth;
+                while (dp > 0 && n < kWaypoints - 1 && nd > 0 && (int64_t)nd < a.trie_stride) {
+                    wp_node[n] = nd;
+                    wp_depth[n] = dp;
+                    ++n;
+                    const TrieNode tn = trie[nd];
+                    nd = tn.xup;
+                    dp = (dp - 1) & ~7;
+                }
+                const bool ok = nd > 0 && (int64_t)nd < a.trie_stride;
+                wp_node[n] = nd;  // where the next batch starts
+                wp_depth[n] = ok ? dp : 0;
+                sh_nnew = n;
+            }
+            __syncthreads();
+            const int n = sh_nnew;
+            if (tid < n) {
+                int nd = wp_node[tid];
+                int dp = wp_depth[tid];
+                const int stop = wp_depth[tid + 1];
+                while (dp > stop && nd > 0 && (int64_t)nd < a.trie_stride) {
+                    const TrieNode tn = trie[nd];
+                    dst[dp - 1] = tn.tok;
+                    nd = tn.parent;
+                    --dp;
+                }
+            }
+            node = wp_node[n];
+            depth = wp_depth[n];
+            __syncthreads();
         }
     }
 
@@ -664,7 +1061,9 @@ hipError_t launch_beam(const int32_t* lengths, int32_t B, int32_t T, int32_t V,
     a.B = B;
     a.T = T;
     a.V = V;
-    a.fpb = frames_per_block(V);
+    int pg = pack_group(V), sh = 0;
+    while ((1 << sh) < pg) ++sh;
+    a.pg_shift = sh;
     a.beam = p.beam;
     a.lm_in_lds = (p.lm_table != nullptr && (size_t)V * V * sizeof(float) <= 16384) ? 1 : 0;
     a.out_tokens = out_tokens;
@@ -678,7 +1077,13 @@ hipError_t launch_beam(const int32_t* lengths, int32_t B, int32_t T, int32_t V,
     a.nbest_pnb = p.nbest_pnb;
     size_t dyn = lm_lds_offset(V);
     if (a.lm_in_lds) dyn += (size_t)V * V * sizeof(float);
-    hipLaunchKernelGGL(beam_kernel, dim3((unsigned)B), dim3(kThreads), dyn, stream, a);
+    if (p.lm_table == nullptr)
+        hipLaunchKernelGGL(beam_kernel<kLmNone>, dim3((unsigned)B), dim3(kThreads), dyn, stream, a);
+    else if (a.lm_in_lds)
+        hipLaunchKernelGGL(beam_kernel<kLmLds>, dim3((unsigned)B), dim3(kThreads), dyn, stream, a);
+    else
+        hipLaunchKernelGGL(beam_kernel<kLmGlobal>, dim3((unsigned)B), dim3(kThreads), dyn, stream,
+                           a);
     return hipGetLastError();
 }
 

@@ -16,28 +16,43 @@ struct alignas(8) Survivor {
     float lp;
 };
 
-// Per-frame header written by the prune stage.
-struct alignas(16) FrameHdr {
-    int32_t count;   // |S_t| (0 for frames at or beyond the utterance length)
-    uint32_t offset; // first record, relative to the frame block's record region
-    float top;       // max_v lp[t][v]
+// Survivors kept inside the frame header itself, so that the beam kernel needs a
+// second, dependent load only for frames with more survivors than this.
+constexpr int kInlineSurvivors = 6;
+
+// Per-frame header written by the prune stage (one 64-byte line).
+struct alignas(64) FrameHdr {
+    int32_t count;    // |S_t| (0 for frames at or beyond the utterance length)
+    uint32_t offset;  // first record, relative to the frame's pack group region
+    float top;        // max_v lp[t][v]
     int32_t pad;
+    Survivor first[kInlineSurvivors];  // copies of records 0..min(count,6)-1
 };
+static_assert(sizeof(FrameHdr) == 64, "FrameHdr must be one 64-byte line");
 
 // One node of the prefix trie (global memory): a prefix is a chain of nodes.
-struct alignas(8) TrieNode {
+// `xup` is the nearest ancestor whose depth is a multiple of 8 (strictly above
+// this node), so the final back-walk takes depth/8 dependent loads and the
+// 8-token segments in between are walked in parallel.
+struct alignas(16) TrieNode {
     int32_t parent;
+    int32_t xup;
     int32_t tok;
+    int32_t depth;
 };
 
-// Frames handled by one workgroup of the prune stage.  Survivor records of a
-// block are packed densely from the block's region base = block * fpb * V.
-__host__ __device__ inline int32_t frames_per_block(int32_t V) {
-    int32_t f = 8192 / V;
-    if (f < 1) f = 1;
-    if (f > 256) f = 256;
-    return f;
+// Lanes of a wavefront that own one frame in the prune stage: the smallest power
+// of two >= ceil(V/4), at most 64.
+__host__ __device__ inline int32_t lanes_per_frame(int32_t V) {
+    const int32_t q = (V + 3) / 4;
+    int32_t l = 1;
+    while (l < q && l < 64) l <<= 1;
+    return l;
 }
+
+// Frames whose survivor records are packed back to back (one wavefront round of
+// the prune stage); records of pack group p start at p * pack_group * V.
+__host__ __device__ inline int32_t pack_group(int32_t V) { return 64 / lanes_per_frame(V); }
 
 struct Workspace {
     FrameHdr* hdr;      // [B*T]

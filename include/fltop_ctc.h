@@ -140,12 +140,14 @@ int fltop_ctc_search(const int32_t* lengths, int32_t B, int32_t T, int32_t V,
                      fltop_stats* stats, void* hip_stream);
 
 /* Copy the survivor lists fltop_ctc_prune left in `workspace` into plain
- * arrays: counts dev [B*T] int32 (0 for frames beyond the length), tokens dev
- * [B*T,V] int32 and values dev [B*T,V] fp32 (first counts[f] entries of row f,
- * ascending token id, rest untouched), frame_max dev [B*T] fp32 (NULL to skip). */
+ * arrays (for inspection and tests): counts dev [B*T] int32 (0 for frames at or
+ * beyond lengths[b]), tokens dev [B*T,V] int32 and values dev [B*T,V] fp32
+ * (first counts[f] entries of row f, ascending token id, rest untouched),
+ * frame_max dev [B*T] fp32 (NULL to skip).  `lengths` as given to
+ * fltop_ctc_prune. */
 int fltop_ctc_unpack_survivors(const void* workspace, size_t workspace_bytes,
-                               int32_t B, int32_t T, int32_t V, int32_t beam,
-                               int32_t* counts, int32_t* tokens, float* values,
+                               const int32_t* lengths, int32_t B, int32_t T, int32_t V,
+                               int32_t beam, int32_t* counts, int32_t* tokens, float* values,
                                float* frame_max, void* hip_stream);
 
 /* Human-readable name of a status code (static storage). */

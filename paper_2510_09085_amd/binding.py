@@ -71,7 +71,7 @@ def load():
     lib.fltop_ctc_prune.restype = ctypes.c_int
     lib.fltop_ctc_prune.argtypes = [vp, vp, i32, i32, i32, i32, f32, vp, sz, vp]
     lib.fltop_ctc_unpack_survivors.restype = ctypes.c_int
-    lib.fltop_ctc_unpack_survivors.argtypes = [vp, sz, i32, i32, i32, i32, vp, vp, vp, vp, vp]
+    lib.fltop_ctc_unpack_survivors.argtypes = [vp, sz, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp]
     lib.fltop_status_string.restype = ctypes.c_char_p
     lib.fltop_status_string.argtypes = [ctypes.c_int]
     _lib = lib
@@ -208,14 +208,16 @@ def prune(logprobs: torch.Tensor, lengths: torch.Tensor, beam: int, rel_threshol
     return workspace
 
 
-def unpack_survivors(workspace: torch.Tensor, B: int, T: int, V: int, beam: int, stream=None):
+def unpack_survivors(workspace: torch.Tensor, lengths: torch.Tensor, B: int, T: int, V: int,
+                     beam: int, stream=None):
     """fltop_ctc_unpack_survivors -> (counts [B*T], tokens [B*T,V], values [B*T,V], frame_max [B*T])."""
     dev = workspace.device
     counts = torch.zeros(B * T, dtype=torch.int32, device=dev)
     tokens = torch.full((B * T, V), -1, dtype=torch.int32, device=dev)
     values = torch.zeros((B * T, V), dtype=torch.float32, device=dev)
     fmax = torch.zeros(B * T, dtype=torch.float32, device=dev)
-    rc = int(load().fltop_ctc_unpack_survivors(_ptr(workspace), workspace.numel(), B, T, V,
+    rc = int(load().fltop_ctc_unpack_survivors(_ptr(workspace), workspace.numel(),
+                                               _ptr(lengths), B, T, V,
                                                int(beam), _ptr(counts), _ptr(tokens),
                                                _ptr(values), _ptr(fmax), _stream_handle(stream)))
     if rc != 0:

@@ -54,18 +54,19 @@ extern "C" int fltop_ctc_prune(const float* logprobs, const int32_t* lengths, in
     return e == hipSuccess ? FLTOP_OK : FLTOP_ERR_HIP;
 }
 
-extern "C" int fltop_ctc_unpack_survivors(const void* workspace, size_t workspace_bytes, int32_t B,
-                                          int32_t T, int32_t V, int32_t beam, int32_t* counts,
+extern "C" int fltop_ctc_unpack_survivors(const void* workspace, size_t workspace_bytes,
+                                          const int32_t* lengths, int32_t B, int32_t T,
+                                          int32_t V, int32_t beam, int32_t* counts,
                                           int32_t* tokens, float* values, float* frame_max,
                                           void* hip_stream) {
-    if (!counts || !tokens || !values) return FLTOP_ERR_NULL_POINTER;
+    if (!lengths || !counts || !tokens || !values) return FLTOP_ERR_NULL_POINTER;
     int rc = check_shapes(B, T, V, beam);
     if (rc != FLTOP_OK) return rc;
     rc = check_workspace(workspace, workspace_bytes, fltop_ctc_workspace_bytes(B, T, V, beam));
     if (rc != FLTOP_OK) return rc;
     const fltop::Workspace ws =
         fltop::carve_workspace(const_cast<void*>(workspace), B, T, V, beam);
-    hipError_t e = fltop::launch_unpack(ws, B, T, V, counts, tokens, values, frame_max,
+    hipError_t e = fltop::launch_unpack(ws, lengths, B, T, V, counts, tokens, values, frame_max,
                                         static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? FLTOP_OK : FLTOP_ERR_HIP;
 }

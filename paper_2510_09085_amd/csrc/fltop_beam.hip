@@ -76,7 +76,7 @@ struct BeamArgs {
     const float* lm_table;  // global copy (always valid when LM is on)
     const float* lm_bound;
     double lm_alpha, lm_beta;
-    int32_t B, T, V, pg_shift, beam;
+    int32_t B, T, V, beam;
     int32_t lm_in_lds;  // 1: table staged into LDS
     int32_t* out_tokens;
     int32_t* out_lengths;
@@ -192,7 +192,7 @@ __host__ __device__ inline size_t lm_lds_offset(int V) {
 // What a frame header holds besides survivors 2..5 (one 32-byte LDS read).
 struct HdrHead {
     int32_t count;
-    uint32_t offset;
+    int32_t reserved;
     float top;
     int32_t pad;
     Survivor s0, s1;
@@ -452,7 +452,6 @@ __global__ __launch_bounds__(kThreads) void beam_kernel(BeamArgs a) {
     len = len < 0 ? 0 : (len > a.T ? a.T : len);
     const int64_t g_base = (int64_t)b * a.T;
     const Survivor* rec_all = a.rec;
-    const int pg_shift = a.pg_shift;
 
     // ---- header chunks: 32 frames x 64 B = 128 threads x 16 B ------------------------
     // Chunk c+1 is loaded into registers while chunk c is decoded and moved into LDS at
@@ -464,8 +463,6 @@ __global__ __launch_bounds__(kThreads) void beam_kernel(BeamArgs a) {
         if (tid < 4 * kChunk && (c) * kChunk + (tid >> 2) < len)                         \
             (dst) = hdr_words[(int64_t)(c) * (4 * kChunk) + tid];                        \
     } while (0)
-#define FLTOP_REC_BASE(g, offset) \
-    (rec_all + ((((g) >> pg_shift) << pg_shift) * (int64_t)V) + (offset))
 #define FLTOP_RING_HEAD(t) (*reinterpret_cast<const HdrHead*>(&ring[(t) % kChunk]))
 
     uint4 staged;
@@ -606,9 +603,10 @@ __global__ __launch_bounds__(kThreads) void beam_kernel(BeamArgs a) {
             sh_blcount = 0;
         }
         if (big) {
-            const Survivor* recs = FLTOP_REC_BASE(g, hd.offset);
+            const Survivor* recs = rec_all + g * (int64_t)V;
+            const FrameHdr* full = &ring[t % kChunk];
             for (int k = tid; k < K; k += kThreads) {
-                const Survivor s = recs[k];
+                const Survivor s = (k < kRegK) ? full->first[k] : recs[k];
                 s_tok[k] = (uint16_t)s.tok;
                 dense_lp[s.tok] = s.lp;
             }
@@ -919,7 +917,6 @@ __global__ __launch_bounds__(kThreads) void beam_kernel(BeamArgs a) {
     }  // frames of the chunk
     }  // chunks
 #undef FLTOP_LOAD_CHUNK
-#undef FLTOP_REC_BASE
 #undef FLTOP_RING_HEAD
 
     // every trie store must have landed before the back-walk reads the nodes
@@ -1061,9 +1058,6 @@ hipError_t launch_beam(const int32_t* lengths, int32_t B, int32_t T, int32_t V,
     a.B = B;
     a.T = T;
     a.V = V;
-    int pg = pack_group(V), sh = 0;
-    while ((1 << sh) < pg) ++sh;
-    a.pg_shift = sh;
     a.beam = p.beam;
     a.lm_in_lds = (p.lm_table != nullptr && (size_t)V * V * sizeof(float) <= 16384) ? 1 : 0;
     a.out_tokens = out_tokens;

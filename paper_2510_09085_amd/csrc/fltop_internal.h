@@ -16,17 +16,18 @@ struct alignas(8) Survivor {
     float lp;
 };
 
-// Survivors kept inside the frame header itself, so that the beam kernel needs a
-// second, dependent load only for frames with more survivors than this.
+// Survivors kept inside the frame header itself (ranks 0..5 in ascending token
+// order).  Further survivors of a frame live in the record array at a fixed
+// place: frame g owns records [g*V, g*V + V), survivor of rank k >= 6 in slot k.
 constexpr int kInlineSurvivors = 6;
 
 // Per-frame header written by the prune stage (one 64-byte line).
 struct alignas(64) FrameHdr {
-    int32_t count;    // |S_t| (0 for frames at or beyond the utterance length)
-    uint32_t offset;  // first record, relative to the frame's pack group region
-    float top;        // max_v lp[t][v]
+    int32_t count;     // |S_t| (0 for frames at or beyond the utterance length)
+    int32_t reserved;  // 0
+    float top;         // max_v lp[t][v]
     int32_t pad;
-    Survivor first[kInlineSurvivors];  // copies of records 0..min(count,6)-1
+    Survivor first[kInlineSurvivors];  // survivors 0..min(count,6)-1, ascending token
 };
 static_assert(sizeof(FrameHdr) == 64, "FrameHdr must be one 64-byte line");
 
@@ -50,13 +51,9 @@ __host__ __device__ inline int32_t lanes_per_frame(int32_t V) {
     return l;
 }
 
-// Frames whose survivor records are packed back to back (one wavefront round of
-// the prune stage); records of pack group p start at p * pack_group * V.
-__host__ __device__ inline int32_t pack_group(int32_t V) { return 64 / lanes_per_frame(V); }
-
 struct Workspace {
     FrameHdr* hdr;      // [B*T]
-    Survivor* rec;      // [B*T*V] capacity, densely packed per frame block
+    Survivor* rec;      // [B*T][V]: survivors of rank >= 6 (slot = rank)
     TrieNode* trie;     // [B][trie_stride]
     float* lm_bound;    // [1] upper bound of lm_weight*table+bonus (or 0)
     int64_t trie_stride;
@@ -86,8 +83,9 @@ inline Workspace carve_workspace(void* base, int32_t B, int32_t T, int32_t V, in
 // Launchers (defined next to their kernels); each returns a hipError_t.
 hipError_t launch_prune(const float* logprobs, const int32_t* lengths, int32_t B, int32_t T,
                         int32_t V, float ln_r, const Workspace& ws, hipStream_t stream);
-hipError_t launch_unpack(const Workspace& ws, int32_t B, int32_t T, int32_t V, int32_t* counts,
-                         int32_t* tokens, float* values, float* frame_max, hipStream_t stream);
+hipError_t launch_unpack(const Workspace& ws, const int32_t* lengths, int32_t B, int32_t T,
+                         int32_t V, int32_t* counts, int32_t* tokens, float* values,
+                         float* frame_max, hipStream_t stream);
 hipError_t launch_lm_bound(const float* lm_table, int32_t V, float lm_weight, float bonus,
                            float* out, hipStream_t stream);
 hipError_t launch_beam(const int32_t* lengths, int32_t B, int32_t T, int32_t V,

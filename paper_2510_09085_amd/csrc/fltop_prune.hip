@@ -4,15 +4,17 @@
 // batch at once, ahead of the beam search, and is bound by the HBM read of the
 // emissions.
 //
-// Output per frame: a header (count, record offset, top emission) and the
-// surviving (token, log-prob) records in ascending token order.
+// Output per frame: a 64-byte header (count, top emission, survivors 0..5 in
+// ascending token order) and, for frames with more than six survivors, survivors
+// 6.. as (token, log-prob) records at a fixed place (slot = rank).
 //
 // Mapping: a frame is owned by LPF lanes of one wavefront (LPF = 1..64, a power
-// of two >= V/4), each lane holding 4*ITERS consecutive-in-chunks values in
-// registers, so a wavefront handles 64/LPF frames per round with one coalesced
-// 16-byte load per lane.  Max, threshold, ballot and prefix sums are wave-local:
-// no LDS, no barrier.  The records of one round's frames (a "pack group") are
-// written back to back, so the beam kernel reads a contiguous stream.
+// of two >= V/4), each lane holding 4*ITERS values in registers, so a wavefront
+// handles 64/LPF frames per round with one coalesced 16-byte load per lane and
+// chunk.  Max, threshold and the prefix sums that place the survivors are
+// wave-local DPP operations; LDS is used only as a wave-private staging area for
+// the headers (no barrier).  Wavefronts walk the frames of an utterance with a
+// grid stride and load the next rounds before working on the current ones.
 #include "fltop_internal.h"
 
 namespace fltop {
@@ -21,155 +23,241 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kWave = 64;
 constexpr int kWaves = kThreads / kWave;
-constexpr int kRoundsPerWave = 4;  // consecutive pack groups handled by one wavefront
 
-__device__ inline float wave_max_f(float x) {
-#pragma unroll
-    for (int o = kWave / 2; o > 0; o >>= 1) x = fmaxf(x, __shfl_xor(x, o, kWave));
-    return x;
+// Value of `v` in the lane selected by a DPP control word; `old` where that lane
+// does not exist or the row is masked off.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ int dpp_int(int old, int v) {
+    return __builtin_amdgcn_update_dpp(old, v, CTRL, ROW_MASK, 0xf, false);
+}
+template <int CTRL>
+__device__ __forceinline__ float dpp_float(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(v), __float_as_int(v), CTRL,
+                                                      0xf, 0xf, false));
 }
 
-__device__ inline int below(uint64_t mask, int lane) {
-    return __popcll(mask & ((1ull << lane) - 1ull));
-}
-
-// max over the LPF lanes of a frame's lane group (groups are LPF-aligned)
+// Max over the LPF lanes of a frame's lane group (groups are LPF-aligned); every lane of
+// the group ends up with the result.  Steps 1, 2 use quad permutes, 4 the half-row
+// mirror, 8 the row mirror (a mirror pairs each lane with one of the other half, which
+// is all a max needs); 16 and 32 go through the cross-lane network.
 template <int LPF>
-__device__ inline float group_max(float x) {
-#pragma unroll
-    for (int o = LPF / 2; o > 0; o >>= 1) x = fmaxf(x, __shfl_xor(x, o, kWave));
+__device__ __forceinline__ float group_max(float x) {
+    if (LPF >= 2) x = fmaxf(x, dpp_float<0xB1>(x));   // quad_perm [1,0,3,2]
+    if (LPF >= 4) x = fmaxf(x, dpp_float<0x4E>(x));   // quad_perm [2,3,0,1]
+    if (LPF >= 8) x = fmaxf(x, dpp_float<0x141>(x));  // row_half_mirror
+    if (LPF >= 16) x = fmaxf(x, dpp_float<0x140>(x)); // row_mirror
+    if (LPF >= 32) x = fmaxf(x, __shfl_xor(x, 16, kWave));
+    if (LPF >= 64) x = fmaxf(x, __shfl_xor(x, 32, kWave));
     return x;
+}
+
+// Inclusive prefix sum of `c` over the lanes of each LPF-lane group.  Every DPP read is
+// executed by all lanes (never inside a lane-dependent branch: a lane that is switched
+// off cannot be read), and masked afterwards.
+template <int LPF>
+__device__ __forceinline__ int group_inclusive_scan(int c, int lg) {
+    int v = c;
+    if (LPF >= 2) {
+        const int up = dpp_int<0x111, 0xf>(0, v);  // row_shr:1
+        v += (lg >= 1) ? up : 0;
+    }
+    if (LPF >= 4) {
+        const int up = dpp_int<0x112, 0xf>(0, v);  // row_shr:2
+        v += (lg >= 2) ? up : 0;
+    }
+    if (LPF >= 8) {
+        const int up = dpp_int<0x114, 0xf>(0, v);  // row_shr:4
+        v += (lg >= 4) ? up : 0;
+    }
+    if (LPF >= 16) {
+        const int up = dpp_int<0x118, 0xf>(0, v);  // row_shr:8
+        v += (lg >= 8) ? up : 0;
+    }
+    if (LPF >= 32) v += dpp_int<0x142, 0xa>(0, v);  // lane 15 of rows 0,2 into rows 1,3
+    if (LPF >= 64) v += dpp_int<0x143, 0xc>(0, v);  // lane 31 into rows 2,3
+    return v;
+}
+
+template <int LPF, int ITERS, bool VEC4>
+struct FrameRegs {
+    float x[ITERS][4];
+    bool valid;
+};
+
+// Load the values of frame `t` of one utterance (row = first emission of that frame).
+template <int LPF, int ITERS, bool VEC4>
+__device__ __forceinline__ void load_frame(FrameRegs<LPF, ITERS, VEC4>& r,
+                                           const float* __restrict__ row, bool valid, int32_t V,
+                                           int lg) {
+    r.valid = valid;
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+        const int v0 = 4 * (lg + LPF * it);
+        if (VEC4) {
+            float4 q = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+            if (valid && v0 < V) q = *reinterpret_cast<const float4*>(row + v0);
+            r.x[it][0] = q.x;
+            r.x[it][1] = q.y;
+            r.x[it][2] = q.z;
+            r.x[it][3] = q.w;
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                r.x[it][e] = (valid && v0 + e < V) ? row[v0 + e] : -INFINITY;
+        }
+    }
 }
 
 template <int LPF, int ITERS, bool VEC4>
 __global__ __launch_bounds__(kThreads) void prune_kernel(
     const float* __restrict__ logprobs, const int32_t* __restrict__ lengths, int32_t B, int32_t T,
     int32_t V, float ln_r, FrameHdr* __restrict__ hdr, Survivor* __restrict__ rec) {
-    constexpr int FPR = kWave / LPF;  // frames per wave round = pack group size
+    constexpr int FPR = kWave / LPF;  // frames per wave round
     static_assert(LPF == kWave || ITERS == 1, "several chunks per lane only for whole-wave frames");
+    static_assert(ITERS <= 8 || ITERS == 16, "flag word holds 4*ITERS <= 64 bits");
+    __shared__ FrameHdr stage[kWaves][FPR];  // header images of one round, per wavefront
     const int lane = threadIdx.x & (kWave - 1);
     const int lg = lane & (LPF - 1);  // lane within the frame's group
     const int gw = lane / LPF;        // group within the wave
-    const int64_t total_frames = (int64_t)B * T;
-    const int64_t wave_id = (int64_t)blockIdx.x * kWaves + threadIdx.x / kWave;
-    const uint64_t group_mask =
-        (LPF == kWave) ? ~0ull : (((1ull << LPF) - 1ull) << (gw * LPF));
+    // blockIdx.y walks the utterances: no division, and rounds beyond a length are not run
+    for (int32_t b = blockIdx.y; b < B; b += gridDim.y) {
+    int32_t len = lengths[b];
+    len = len < 0 ? 0 : (len > T ? T : len);
+    const int n_rounds = (len + FPR - 1) / FPR;
+    const int wave_id = blockIdx.x * kWaves + threadIdx.x / kWave;
+    const int n_waves = gridDim.x * kWaves;
+    const int64_t g_base = (int64_t)b * T;
+    const float* utt = logprobs + g_base * V;
 
-#pragma unroll 1
-    for (int rd = 0; rd < kRoundsPerWave; ++rd) {
-        const int64_t pack = wave_id * kRoundsPerWave + rd;  // pack group index
-        const int64_t g_first = pack * FPR;
-        if (g_first >= total_frames) break;
-        const int64_t g = g_first + gw;
-        bool valid = g < total_frames;
-        if (valid) {
-            const int32_t b = (int32_t)(g / T);
-            const int32_t t = (int32_t)(g - (int64_t)b * T);
-            int32_t len = lengths[b];
-            len = len < 0 ? 0 : (len > T ? T : len);
-            valid = t < len;
-        }
-        // ---- load this lane's values ------------------------------------------------
-        float x[ITERS][4];
-        const float* row = logprobs + g * V;
+    // U rounds are loaded together (more bytes in flight per wavefront), one batch ahead
+    constexpr int U = ITERS >= 4 ? 1 : (ITERS == 2 ? 2 : 4);
+    FrameRegs<LPF, ITERS, VEC4> cur[U], nxt[U];
 #pragma unroll
-        for (int it = 0; it < ITERS; ++it) {
-            const int v0 = 4 * (lg + LPF * it);
-            if (VEC4) {
-                float4 q = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
-                if (valid && v0 < V) q = *reinterpret_cast<const float4*>(row + v0);
-                x[it][0] = q.x;
-                x[it][1] = q.y;
-                x[it][2] = q.z;
-                x[it][3] = q.w;
-            } else {
+    for (int u = 0; u < U; ++u) {
+        const int t = (wave_id * U + u) * FPR + gw;
+        load_frame(cur[u], utt + (int64_t)t * V, t < len, V, lg);
+    }
+
+    for (int base = wave_id * U; base < n_rounds; base += n_waves * U) {
+        // next batch's loads go out before this batch's work
+        const int base_next = base + n_waves * U;
 #pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    x[it][e] = (valid && v0 + e < V) ? row[v0 + e] : -INFINITY;
-            }
+        for (int u = 0; u < U; ++u) {
+            const int t = (base_next + u) * FPR + gw;
+            load_frame(nxt[u], utt + (int64_t)t * V, t < len, V, lg);
         }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+        const int rd = base + u;
+        if (rd >= n_rounds) break;
+        const int64_t g = g_base + rd * FPR + gw;
+        const FrameRegs<LPF, ITERS, VEC4>& fr = cur[u];
         // ---- top emission and threshold ------------------------------------------------
         float m = -INFINITY;
 #pragma unroll
         for (int it = 0; it < ITERS; ++it)
 #pragma unroll
-            for (int e = 0; e < 4; ++e) m = fmaxf(m, x[it][e]);
-        m = (LPF == kWave) ? wave_max_f(m) : group_max<LPF>(m);
+            for (int e = 0; e < 4; ++e) m = fmaxf(m, fr.x[it][e]);
+        m = group_max<LPF>(m);
         const float thr = m + ln_r;  // one fp32 add
-        // ---- survivors, packed over the whole round in (frame, token) order -----------
-        Survivor* region = rec + g_first * V;
-        int running = 0;       // records written by earlier chunks of this round
-        int frame_count = 0;   // survivors of this lane's frame
-        int frame_offset = 0;  // first record of this lane's frame
+
+        // ---- survivors in ascending token order: rank = survivors before it in the frame.
+        // Ranks 0..5 go into the header, ranks >= 6 into the frame's record list (slot =
+        // rank), so every store is decided by the lane's own rank.  The headers of the
+        // round's frames are assembled in LDS (wave-local, no barrier) and leave as
+        // whole 64-byte lines, 16 bytes per lane: a partly written line would cost the
+        // memory system a read-modify-write.
+        Survivor* list = rec + g * V;
+        FrameHdr* img = &stage[threadIdx.x / kWave][gw];
+        int total = 0;
 #pragma unroll
         for (int it = 0; it < ITERS; ++it) {
             const int v0 = 4 * (lg + LPF * it);
-            bool keep[4];
-            uint64_t mk[4];
+            unsigned bits = 0;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                keep[e] = valid && (v0 + e < V) && (x[it][e] >= thr);
-                mk[e] = __ballot(keep[e]);
+            for (int e = 0; e < 4; ++e)
+                bits |= (fr.valid && (v0 + e < V) && (fr.x[it][e] >= thr)) ? (1u << e) : 0u;
+            const int cnt = __popc(bits);
+            const int incl = group_inclusive_scan<LPF>(cnt, lg);
+            int rank = total + incl - cnt;
+            while (bits != 0) {  // usually zero or one survivor per lane
+                const int e = __ffs(bits) - 1;
+                bits &= bits - 1;
+                Survivor s;
+                s.tok = v0 + e;
+                s.lp = e == 0 ? fr.x[it][0] : e == 1 ? fr.x[it][1] : e == 2 ? fr.x[it][2] : fr.x[it][3];
+                if (rank < kInlineSurvivors)
+                    img->first[rank] = s;
+                else
+                    list[rank] = s;
+                ++rank;
             }
-            int pos = running;  // records of lower lanes (all four slots) + my lower slots
-#pragma unroll
-            for (int e = 0; e < 4; ++e) pos += below(mk[e], lane);
-            int in_group = 0, before_group = 0, all = 0;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                in_group += __popcll(mk[e] & group_mask);
-                before_group += below(mk[e], gw * LPF);
-                all += __popcll(mk[e]);
+            if (LPF == kWave) {
+                total += __builtin_amdgcn_readlane(incl, kWave - 1);
+            } else {
+                total = incl;  // exact in the group's last lane, which writes the header
             }
-            if (it == 0) frame_offset = running + before_group;
-            int mine = 0;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                if (keep[e]) {
-                    Survivor s;
-                    s.tok = v0 + e;
-                    s.lp = x[it][e];
-                    region[pos + mine] = s;
-                    const int in_frame = pos + mine - frame_offset;  // rank within the frame
-                    if (in_frame < kInlineSurvivors) hdr[g].first[in_frame] = s;
-                    ++mine;
-                }
-            }
-            frame_count += in_group;
-            running += all;
         }
-        if (lg == 0 && g < total_frames) {
+        if (lg == LPF - 1) {
             int4 h;
-            h.x = frame_count;
-            h.y = frame_offset;
-            h.z = __float_as_int(valid ? m : 0.0f);
+            h.x = total;
+            h.y = 0;
+            h.z = __float_as_int(m);
             h.w = 0;
-            *reinterpret_cast<int4*>(&hdr[g]) = h;  // count, offset, top, pad
+            *reinterpret_cast<int4*>(img) = h;  // count, reserved, top, pad
         }
+        // LDS operations of one wavefront execute in order, so the images are complete
+        // for the reads below.  Frames beyond the length get no header: never read, and
+        // the slots past T belong to the next utterance.
+        {
+            const int4* src = reinterpret_cast<const int4*>(&stage[threadIdx.x / kWave][0]);
+            int4* dst = reinterpret_cast<int4*>(hdr + g_base + (int64_t)rd * FPR);
+#pragma unroll
+            for (int p0 = 0; p0 < 4 * FPR; p0 += kWave) {
+                const int p = p0 + lane;
+                if (p < 4 * FPR && rd * FPR + (p >> 2) < len) dst[p] = src[p];
+            }
+        }
+        }  // rounds of the batch
+#pragma unroll
+        for (int u = 0; u < U; ++u) cur[u] = nxt[u];
     }
+    }  // utterances
 }
 
 __global__ __launch_bounds__(kThreads) void unpack_kernel(
-    const FrameHdr* __restrict__ hdr, const Survivor* __restrict__ rec, int64_t total_frames,
-    int32_t V, int32_t pg, int32_t* __restrict__ counts, int32_t* __restrict__ tokens,
-    float* __restrict__ values, float* __restrict__ frame_max) {
+    const FrameHdr* __restrict__ hdr, const Survivor* __restrict__ rec,
+    const int32_t* __restrict__ lengths, int64_t total_frames, int32_t T, int32_t V,
+    int32_t* __restrict__ counts, int32_t* __restrict__ tokens, float* __restrict__ values,
+    float* __restrict__ frame_max) {
     const int lane = threadIdx.x & (kWave - 1);
     const int64_t g = (int64_t)blockIdx.x * kWaves + threadIdx.x / kWave;
     if (g >= total_frames) return;
-    struct Head { int32_t count; uint32_t offset; float top; int32_t pad; };
+    const int32_t b = (int32_t)(g / T);
+    const int32_t t = (int32_t)(g - (int64_t)b * T);
+    int32_t len = lengths[b];
+    len = len < 0 ? 0 : (len > T ? T : len);
+    if (t >= len) {  // no header was written for this frame
+        if (lane == 0) {
+            counts[g] = 0;
+            if (frame_max) frame_max[g] = 0.0f;
+        }
+        return;
+    }
+    struct Head {
+        int32_t count;
+        int32_t reserved;
+        float top;
+        int32_t pad;
+    };
     const Head h = *reinterpret_cast<const Head*>(&hdr[g]);
     if (lane == 0) {
         counts[g] = h.count;
         if (frame_max) frame_max[g] = h.top;
     }
-    const Survivor* src = rec + (g / pg) * (int64_t)pg * V + h.offset;
+    const Survivor* src = rec + g * V;
     for (int k = lane; k < h.count; k += kWave) {
-        Survivor s = src[k];
-        if (k < kInlineSurvivors) {
-            const Survivor in = hdr[g].first[k];
-            // the two copies must agree bit for bit; a mismatch is made visible
-            if (in.tok != s.tok || __float_as_int(in.lp) != __float_as_int(s.lp)) s.tok = -2;
-        }
+        const Survivor s = (k < kInlineSurvivors) ? hdr[g].first[k] : src[k];
         tokens[g * V + k] = s.tok;
         values[g * V + k] = s.lp;
     }
@@ -182,7 +270,7 @@ __global__ __launch_bounds__(kThreads) void lm_bound_kernel(const float* __restr
     __shared__ float s_part[kWaves];
     float m = -INFINITY;
     for (int64_t i = threadIdx.x; i < n; i += kThreads) m = fmaxf(m, fmaf(w, table[i], bonus));
-    m = wave_max_f(m);
+    m = group_max<kWave>(m);
     if ((threadIdx.x & (kWave - 1)) == 0) s_part[threadIdx.x / kWave] = m;
     __syncthreads();
     if (threadIdx.x == 0) {
@@ -195,19 +283,22 @@ template <int LPF, int ITERS>
 hipError_t launch_prune_t(const float* logprobs, const int32_t* lengths, int32_t B, int32_t T,
                           int32_t V, float ln_r, const Workspace& ws, hipStream_t stream) {
     constexpr int FPR = kWave / LPF;
-    const int64_t frames = (int64_t)B * T;
-    const int64_t packs = (frames + FPR - 1) / FPR;
-    const int64_t waves = (packs + kRoundsPerWave - 1) / kRoundsPerWave;
-    const int64_t blocks = (waves + kWaves - 1) / kWaves;
+    constexpr int U = ITERS >= 4 ? 1 : (ITERS == 2 ? 2 : 4);
+    // grid = (blocks per utterance, B): about 2048 workgroups in all (8 per CU), but never
+    // more wavefronts per utterance than it has batches of rounds
+    const int rounds = (T + FPR - 1) / FPR;
+    int bx = (rounds + kWaves * U - 1) / (kWaves * U);
+    const int cap = (2048 + B - 1) / B;
+    if (bx > cap) bx = cap;
+    if (bx < 1) bx = 1;
+    const dim3 grid((unsigned)bx, (unsigned)(B < 65535 ? B : 65535));
     const bool vec4 = (V % 4 == 0) && ((reinterpret_cast<uintptr_t>(logprobs) & 15u) == 0);
     if (vec4)
-        hipLaunchKernelGGL((prune_kernel<LPF, ITERS, true>), dim3((unsigned)blocks),
-                           dim3(kThreads), 0, stream, logprobs, lengths, B, T, V, ln_r, ws.hdr,
-                           ws.rec);
+        hipLaunchKernelGGL((prune_kernel<LPF, ITERS, true>), grid, dim3(kThreads), 0, stream,
+                           logprobs, lengths, B, T, V, ln_r, ws.hdr, ws.rec);
     else
-        hipLaunchKernelGGL((prune_kernel<LPF, ITERS, false>), dim3((unsigned)blocks),
-                           dim3(kThreads), 0, stream, logprobs, lengths, B, T, V, ln_r, ws.hdr,
-                           ws.rec);
+        hipLaunchKernelGGL((prune_kernel<LPF, ITERS, false>), grid, dim3(kThreads), 0, stream,
+                           logprobs, lengths, B, T, V, ln_r, ws.hdr, ws.rec);
     return hipGetLastError();
 }
 
@@ -236,12 +327,13 @@ hipError_t launch_prune(const float* logprobs, const int32_t* lengths, int32_t B
 #undef FLTOP_PRUNE_CASE
 }
 
-hipError_t launch_unpack(const Workspace& ws, int32_t B, int32_t T, int32_t V, int32_t* counts,
-                         int32_t* tokens, float* values, float* frame_max, hipStream_t stream) {
+hipError_t launch_unpack(const Workspace& ws, const int32_t* lengths, int32_t B, int32_t T,
+                         int32_t V, int32_t* counts, int32_t* tokens, float* values,
+                         float* frame_max, hipStream_t stream) {
     const int64_t frames = (int64_t)B * T;
     const int64_t blocks = (frames + kWaves - 1) / kWaves;
     hipLaunchKernelGGL(unpack_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, stream, ws.hdr,
-                       ws.rec, frames, V, pack_group(V), counts, tokens, values, frame_max);
+                       ws.rec, lengths, frames, T, V, counts, tokens, values, frame_max);
     return hipGetLastError();
 }
 

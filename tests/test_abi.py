@@ -112,7 +112,9 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     assert lib.fltop_ctc_prune(None, fake, 2, 10, 32, 8, 0.01, fake, need, None) == -1
     assert lib.fltop_ctc_prune(fake, fake, 2, 10, 32, 8, 2.0, fake, need, None) == -4
     assert lib.fltop_ctc_prune(fake, fake, 2, 10, 32, 8, 0.01, fake, 16, None) == -5
-    assert lib.fltop_ctc_unpack_survivors(fake, need, 2, 10, 32, 8, None, fake, fake, None,
+    assert lib.fltop_ctc_unpack_survivors(fake, need, fake, 2, 10, 32, 8, None, fake, fake, None,
+                                          None) == -1
+    assert lib.fltop_ctc_unpack_survivors(fake, need, None, 2, 10, 32, 8, fake, fake, fake, None,
                                           None) == -1
 
 

@@ -84,7 +84,7 @@ def test_survivor_lists_are_byte_identical(dev, oracle_lib, V):
         ln_d = torch.from_numpy(ln).to(dev)
         ws = binding.prune(lp_d, ln_d, 4, r)
         counts, tokens, values, fmax = [x.cpu().numpy() for x in
-                                        binding.unpack_survivors(ws, B, T, V, 4)]
+                                        binding.unpack_survivors(ws, ln_d, B, T, V, 4)]
         for b in range(B):
             n = ln[b]
             sl = slice(b * T, b * T + n)
@@ -106,9 +106,10 @@ def test_survivor_lists_on_peaky_workload(dev, oracle_lib):
     lp, ln = synth.make_emissions(w, utterances=range(5))
     B, T, V = lp.shape
     for r in w.rel_thresholds:
-        ws = binding.prune(torch.from_numpy(lp).to(dev), torch.from_numpy(ln).to(dev), w.beam, r)
+        ln_d = torch.from_numpy(ln).to(dev)
+        ws = binding.prune(torch.from_numpy(lp).to(dev), ln_d, w.beam, r)
         counts, tokens, values, _ = [x.cpu().numpy() for x in
-                                     binding.unpack_survivors(ws, B, T, V, w.beam)]
+                                     binding.unpack_survivors(ws, ln_d, B, T, V, w.beam)]
         oc, ot, _ = oracle_lib.survivors(lp, r)
         np.testing.assert_array_equal(counts, oc)
         mask = np.arange(V)[None, :] < oc[:, None]

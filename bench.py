@@ -34,6 +34,10 @@ def parse_args():
     ap.add_argument("--skip-cpu-baseline", action="store_true")
     ap.add_argument("--skip-extras", action="store_true",
                     help="only the timed steps and the roofline of this workload")
+    ap.add_argument("--counter-probe", choices=("prune", "search"), default=None,
+                    help="run only that stage a few times (plus, for prune, a plain device copy "
+                         "of known size for calibration): the program to put under "
+                         "`rocprofv3 --pmc ...`")
     return ap.parse_args()
 
 
@@ -150,7 +154,8 @@ def emission_read_roofline(torch, binding, synth, w, r, dev, target_bytes=1 << 3
     gbs = nbytes / (avg * 1e-3) / 1e9
     return {"workload": w.name, "rel_threshold": r, "bound": "hbm", "achieved": round(gbs, 1),
             "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4),
-            "traffic": None, "kernel": "prune_kernel", "avg_launch_us": round(avg * 1e3, 2),
+            "traffic": recorded_traffic("prune_kernel", w.name), "kernel": "prune_kernel",
+            "avg_launch_us": round(avg * 1e3, 2),
             "isolated_launch_us": round(sum(single) / len(single) * 1e3, 2),
             "algorithmic_bytes": nbytes, "written_bytes_approx": prune_written_bytes(st),
             "rotated_copies": copies, "launches": n}
@@ -190,6 +195,66 @@ def cpu_baseline(synth, w, r, frames_budget_s=12.0):
             "pruned_vs_unpruned_speedup": round(fps / fps_unpruned, 2)}
 
 
+def source_digest(*names):
+    """sha256 over the HIP sources a counter file was taken with."""
+    import hashlib
+    h = hashlib.sha256()
+    for n in names:
+        with open(os.path.join(ROOT, "paper_2510_09085_amd", "csrc", n), "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()
+
+
+def recorded_traffic(kernel, workload):
+    """HBM bytes per launch from the rocprofv3 --pmc runs summarised under profiles/
+    (FETCH_SIZE / WRITE_SIZE scaled by a plain copy of known size), or None when there is
+    no record or the kernel source has changed since the counters were taken."""
+    path = os.path.join(ROOT, "profiles", f"traffic_{kernel}_{workload}.json")
+    try:
+        with open(path) as fh:
+            rec = json.load(fh)
+    except (OSError, ValueError):
+        return None
+    if rec.get("source_sha256") != source_digest(*rec.get("sources", [])):
+        return None
+    return rec.get("hbm_bytes_per_launch")
+
+
+def counter_probe(args, torch, binding, synth, dev):
+    """A short, fixed sequence of launches for `rocprofv3 --pmc`."""
+    w = synth.WORKLOADS[args.workload]
+    r = args.rel_threshold
+    out = {"probe": args.counter_probe, "workload": w.name, "rel_threshold": r}
+    srcs = ["fltop_prune.hip", "fltop_internal.h"] if args.counter_probe == "prune" else \
+        ["fltop_beam.hip", "fltop_internal.h"]
+    if args.counter_probe == "prune":
+        copies = 3
+        job = Job(torch, binding, synth, w, dev, copies=copies)
+        st = job.stats_of(job.params(r))
+        n = 6
+        for i in range(n):
+            job.prune(r, copy=i % copies)
+        out.update({"prune_launches": n + 1, "emission_bytes_per_launch": prune_bytes(w, st),
+                    "written_bytes_approx": prune_written_bytes(st)})
+    else:
+        job = Job(torch, binding, synth, w, dev)
+        p = job.params(r)
+        job.prune(r)
+        for _ in range(5):
+            job.search(p)
+        out.update({"search_launches": 5, "frames": job.frames})
+    torch.cuda.synchronize()
+    # calibration: a plain device-to-device copy of 256 MiB reads and writes 256 MiB
+    src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).random_(0, 255)
+    dst = torch.empty_like(src)
+    for _ in range(4):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    out.update({"copy_launches": 4, "copy_bytes_each_way": 256 << 20, "sources": srcs,
+                "source_sha256": source_digest(*srcs)})
+    print(json.dumps(out))
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -205,6 +270,9 @@ def main():
         sys.exit(2)
     binding.load()  # raises if the HIP library has not been built
     dev = torch.device("cuda:0")
+    if args.counter_probe:
+        counter_probe(args, torch, binding, synth, dev)
+        return
     w = synth.WORKLOADS[args.workload]
     r = args.rel_threshold
 
@@ -234,7 +302,8 @@ def main():
     tflops = flops / (search_avg * 1e-3) / 1e12
     roofline = {"kernel": "beam_kernel (search stage)", "bound": "alu",
                 "achieved": round(tflops, 6), "peak": FP64_VECTOR_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(tflops / FP64_VECTOR_TFLOPS, 8), "traffic": None,
+                "frac": round(tflops / FP64_VECTOR_TFLOPS, 8),
+                "traffic": recorded_traffic("beam_kernel", w.name),
                 "avg_launch_us": round(search_avg * 1e3, 2),
                 "algorithmic_flop": flops,
                 "note": "serial chain of T frames per utterance on min(B,256) CUs: "

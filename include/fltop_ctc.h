@@ -88,7 +88,7 @@ typedef struct fltop_stats {
     uint64_t select_passes;     /* histogram passes spent in the top-`beam` selection          */
     uint64_t exact_rankings;    /* selections that needed the exact (score, hash) ranking      */
     uint64_t overflow_drops;    /* entries dropped because a hash collision overfilled a beam  */
-    uint64_t phase_clocks[8];   /* diagnostic: shader-clock cycles per phase of the search stage,
+    uint64_t phase_clocks[16];  /* diagnostic: shader-clock cycles per phase of the search stage,
                                    summed over workgroups; filled only by a library built with
                                    -DFLTOP_PHASE_CLOCKS, otherwise left untouched              */
 } fltop_stats;

@@ -39,7 +39,7 @@ class FltopParams(ctypes.Structure):
 
 STATS_FIELDS = ("frames", "sum_survivors", "sum_candidates", "peak_candidates", "sum_beam",
                 "select_passes", "exact_rankings", "overflow_drops",
-                "clk0", "clk1", "clk2", "clk3", "clk4", "clk5", "clk6", "clk7")
+                *[f"clk{i}" for i in range(16)])
 
 _lib = None
 

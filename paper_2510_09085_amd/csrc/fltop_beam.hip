@@ -519,7 +519,7 @@ __global__ __launch_bounds__(kThreads) void beam_kernel(BeamArgs a) {
     uint64_t st_surv = 0, st_cand = 0, st_peak = 0, st_beam = 0, st_pass = 0, st_exact = 0,
              st_drop = 0;
 #ifdef FLTOP_PHASE_CLOCKS
-    uint64_t ph_clk[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    uint64_t ph_clk[16] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
     uint64_t ph_last = clock64();
 #endif
 
@@ -616,6 +616,7 @@ __global__ __launch_bounds__(kThreads) void beam_kernel(BeamArgs a) {
             dirty = false;
         }
 
+        PHASE_MARK(0);
         fc.nb0 = (K > 0 && surv_tok(fc, 0) == 0) ? 1 : 0;  // records ascend: blank first
         fc.Knb = K - fc.nb0;
         fc.div_magic = fc.Knb > 1 ? (uint32_t)(0x100000000ull / (uint32_t)fc.Knb) + 1u : 0u;
@@ -636,6 +637,7 @@ __global__ __launch_bounds__(kThreads) void beam_kernel(BeamArgs a) {
         int32_t cT0 = 0, cT1 = 0;
         if (e_first < n_ext) cD0 = eval_ext<LM>(fc, e_first, cI0, cT0);
         if (e_first + kThreads < n_ext) cD1 = eval_ext<LM>(fc, e_first + kThreads, cI1, cT1);
+        PHASE_MARK(8);
         // ... and the stay candidate of entry `tid`
         double my_pb = -INFINITY, my_pnb = -INFINITY, my_tot = -INFINITY;
         uint64_t D_stay = kAllOnes;
@@ -834,6 +836,7 @@ __global__ __launch_bounds__(kThreads) void beam_kernel(BeamArgs a) {
                 base = __builtin_amdgcn_readfirstlane(base);
             }
             int slot = base + incl - cnt;
+            PHASE_MARK(9);
             if (sel_s) emit_stay(fc, nxt, lkn, slot++, beam, tid, my_pb, my_pnb, my_tot);
             if (sel_0)
                 emit_ext(fc, nxt, lkn, slot++, beam, t, cD0, cI0, cT0, hh0, hv0, trie, trie_stride);
@@ -891,6 +894,7 @@ __global__ __launch_bounds__(kThreads) void beam_kernel(BeamArgs a) {
                 atomicOr(&lkn->kidmask[p], 1u << (nxt->last[tid] & 31));
             }
         }
+        PHASE_MARK(10);
         // housekeeping behind this frame's last readers: the old generation's links
         // (next used as the new generation of the following frame), the histogram, and
         // the staged survivors
@@ -963,7 +967,7 @@ __global__ __launch_bounds__(kThreads) void beam_kernel(BeamArgs a) {
             atomicAdd((unsigned long long*)&a.stats->exact_rankings, (unsigned long long)st_exact);
             atomicAdd((unsigned long long*)&a.stats->overflow_drops, (unsigned long long)st_drop);
 #ifdef FLTOP_PHASE_CLOCKS
-            for (int i = 0; i < 8; ++i)
+            for (int i = 0; i < 16; ++i)
                 atomicAdd((unsigned long long*)&a.stats->phase_clocks[i],
                           (unsigned long long)ph_clk[i]);
 #endif

@@ -21,8 +21,10 @@
 //  - frame headers (which carry the first six survivors) are staged through LDS
 //    32 frames at a time, one chunk ahead, and barriers wait for LDS traffic only,
 //    so global loads and trie stores stay in flight across them;
-//  - frames whose only survivor is blank change no prefix and no order: every
-//    entry just adds the blank log-prob, with no barrier at all;
+//  - frames whose only survivor is blank change no prefix and no order: their
+//    log-prob goes into one per-utterance offset (scores in LDS are relative to
+//    it) and a flag says that p_b = total, p_nb = -inf holds for every entry;
+//    such a frame touches neither the beam nor a barrier;
 //  - frames with at most six survivors keep them in registers;
 //  - "stay" candidates (which need the log-sum-exps) and extension candidates are
 //    mapped to different wavefronts so that they are evaluated side by side.
@@ -214,6 +216,7 @@ struct FrameCtx {
     double lm_alpha, lm_beta;
     int V;
     bool big;                // survivors staged through LDS
+    bool collapsed;          // blank-only frames came last: read p_b as total, p_nb as -inf
     int nb0;                 // 1 if blank survived (it is record 0 then)
     int Knb;                 // non-blank survivors
     uint32_t div_magic;      // ceil(2^32 / Knb) for e / Knb
@@ -295,14 +298,18 @@ __device__ __forceinline__ uint64_t eval_ext(const FrameCtx& f, int e, int& src_
     const int32_t s = surv_tok(f, f.nb0 + k);
     src_entry = i;
     tok = s;
+    // the four reads go out together; the children list is walked only on a mask hit
     const int32_t li = f.cur->last[i];
-    if ((f.lk->kidmask[i] >> (s & 31)) & 1u) {  // maybe a child i+s is in the beam
+    const uint32_t km = f.lk->kidmask[i];
+    const double pti = f.cur->ptot[i];
+    const double pbi = f.collapsed ? pti : f.cur->pb[i];
+    if ((km >> (s & 31)) & 1u) {  // maybe a child i+s is in the beam
         int guard = 0;
         for (int kid = f.lk->first_kid[i]; kid >= 0 && guard < kMaxBeam;
              kid = f.lk->next_kid[kid], ++guard)
             if (f.cur->last[kid] == s) return kAllOnes;
     }
-    const double src = (s == li) ? f.cur->pb[i] : f.cur->ptot[i];
+    const double src = (s == li) ? pbi : pti;
     const double sc = src + lp_of(f, s) + lm_term<LM>(f, li, s);
     if (!(sc > -INFINITY)) return kAllOnes;
     return f.Rk - order_key(sc);
@@ -328,6 +335,27 @@ __device__ __forceinline__ void hist_add(const FrameCtx& f, const Window& w, uin
     }
     if (x < w.lo) return;
     const int bin = window_bin(w, x);
+    atomicAdd(&hfine[bin], 1u);
+    atomicAdd(&hcoarse[bin >> 4], 1u);
+}
+
+// The same for the candidates beyond the register cache, of which a frame may have
+// thousands.  All that lie beyond the window share the last bin, and one LDS word cannot
+// take that many atomics quickly: those are counted in a register (`n_clamp`) instead.
+__device__ __forceinline__ void hist_add_many(const FrameCtx& f, const Window& w, uint64_t D,
+                                              int se, int32_t tk, uint32_t* hfine,
+                                              uint32_t* hcoarse, int& n_clamp) {
+    uint64_t x = D;
+    if (w.mode != 0) {
+        if (D != w.Dfix) return;
+        x = cand_hash(f, se, tk);
+    }
+    if (x < w.lo) return;
+    const int bin = window_bin(w, x);
+    if (bin == kFine - 1) {
+        ++n_clamp;
+        return;
+    }
     atomicAdd(&hfine[bin], 1u);
     atomicAdd(&hcoarse[bin >> 4], 1u);
 }
@@ -512,8 +540,9 @@ __global__ __launch_bounds__(kThreads) void beam_kernel(BeamArgs a) {
 
     int gen = 0;         // beam generation: slab[gen], links[gen]
     int n_live = 1;
-    bool dirty = false;  // entries were updated in place since the last barrier
-    double kmax_v = 0.0, kmin_v = 0.0;  // bounds of the best / worst score in the beam
+    double bias = 0.0;       // log-mass of the blank-only frames, common to every entry
+    bool collapsed = false;  // blank-only frames since the beam was last written
+    double kmax_v = 0.0, kmin_v = 0.0;  // bounds of the best / worst score (without bias)
 
     // statistics kept by thread 0
     uint64_t st_surv = 0, st_cand = 0, st_peak = 0, st_beam = 0, st_pass = 0, st_exact = 0,
@@ -529,7 +558,6 @@ __global__ __launch_bounds__(kThreads) void beam_kernel(BeamArgs a) {
     lds_barrier();  // nobody still reads the previous chunk's headers
     if (tid < 4 * kChunk) reinterpret_cast<uint4*>(&ring[0])[tid] = staged;
     lds_barrier();
-    dirty = false;
     FLTOP_LOAD_CHUNK(staged, c + 1);
     const int t_end = min(len, (c + 1) * kChunk);
     HdrHead head_next = FLTOP_RING_HEAD(c * kChunk);  // read one frame ahead inside the chunk
@@ -549,16 +577,8 @@ __global__ __launch_bounds__(kThreads) void beam_kernel(BeamArgs a) {
 
         // ---- blank-only frame: no prefix changes, order is preserved -------------------
         if (K == 1 && hd.s0.tok == 0 && hd.s0.lp > -INFINITY) {
-            const double x = (double)hd.s0.lp;
-            if (tid < n_live) {
-                const double nt = cur->ptot[tid] + x;
-                cur->pb[tid] = nt;
-                cur->pnb[tid] = -INFINITY;
-                cur->ptot[tid] = nt;
-            }
-            kmax_v += x;
-            kmin_v += x;
-            dirty = true;
+            bias += (double)hd.s0.lp;
+            collapsed = true;
             if (tid == 0) {
                 st_cand += (uint64_t)n_live;
                 if ((uint64_t)n_live > st_peak) st_peak = (uint64_t)n_live;
@@ -573,6 +593,7 @@ __global__ __launch_bounds__(kThreads) void beam_kernel(BeamArgs a) {
         fc.cur = cur;
         fc.lk = lk;
         fc.big = big;
+        fc.collapsed = collapsed;
         fc.t0 = K > 0 ? hd.s0.tok : -1;
         fc.t1 = K > 1 ? hd.s1.tok : -1;
         fc.l0 = hd.s0.lp;
@@ -611,10 +632,7 @@ __global__ __launch_bounds__(kThreads) void beam_kernel(BeamArgs a) {
                 dense_lp[s.tok] = s.lp;
             }
         }
-        if (big || dirty) {
-            lds_barrier();
-            dirty = false;
-        }
+        if (big) lds_barrier();
 
         PHASE_MARK(0);
         fc.nb0 = (K > 0 && surv_tok(fc, 0) == 0) ? 1 : 0;  // records ascend: blank first
@@ -646,12 +664,13 @@ __global__ __launch_bounds__(kThreads) void beam_kernel(BeamArgs a) {
             const int32_t lj = cur->last[j];
             const double lpl = lp_of(fc, lj);
             my_pb = cur->ptot[j] + lp_blank;
-            const double a1 = cur->pnb[j] + lpl;
+            const double a1 = (collapsed ? -INFINITY : cur->pnb[j]) + lpl;
             double a2 = -INFINITY;
             const int p = lk->par[j];
             if (p >= 0 && lpl > -INFINITY) {
                 const int32_t lpar = cur->last[p];
-                const double src = (lpar == lj) ? cur->pb[p] : cur->ptot[p];
+                const double ptp = cur->ptot[p];
+                const double src = (lpar == lj && !collapsed) ? cur->pb[p] : ptp;
                 a2 = src + lpl + lm_term<LM>(fc, lpar, lj);
             }
             my_pnb = lse2(a1, a2);
@@ -686,13 +705,22 @@ __global__ __launch_bounds__(kThreads) void beam_kernel(BeamArgs a) {
                 if (D_stay != kAllOnes) hist_add(fc, w, D_stay, tid, -1, hfine, hcoarse);
                 if (cD0 != kAllOnes) hist_add(fc, w, cD0, cI0, cT0, hfine, hcoarse);
                 if (cD1 != kAllOnes) hist_add(fc, w, cD1, cI1, cT1, hfine, hcoarse);
-                for (int m = kRegCand; m < M; ++m) {
-                    const int e = e_first + m * kThreads;
-                    if (e >= n_ext) break;
-                    int se;
-                    int32_t tk;
-                    const uint64_t D = eval_ext<LM>(fc, e, se, tk);
-                    if (D != kAllOnes) hist_add(fc, w, D, se, tk, hfine, hcoarse);
+                if (M > kRegCand) {
+                    int n_clamp = 0;
+                    for (int m = kRegCand; m < M; ++m) {
+                        const int e = e_first + m * kThreads;
+                        if (e >= n_ext) break;
+                        int se;
+                        int32_t tk;
+                        const uint64_t D = eval_ext<LM>(fc, e, se, tk);
+                        if (D != kAllOnes)
+                            hist_add_many(fc, w, D, se, tk, hfine, hcoarse, n_clamp);
+                    }
+                    const int wave_clamp = wave_inclusive_scan(n_clamp);  // lane 63: the sum
+                    if (lane == kWave - 1 && wave_clamp > 0) {
+                        atomicAdd(&hfine[kFine - 1], (uint32_t)wave_clamp);
+                        atomicAdd(&hcoarse[kCoarse - 1], (uint32_t)wave_clamp);
+                    }
                 }
                 lds_barrier();
                 PHASE_MARK(2);
@@ -916,6 +944,7 @@ __global__ __launch_bounds__(kThreads) void beam_kernel(BeamArgs a) {
         }
         n_live = n_new;
         gen ^= 1;
+        collapsed = false;  // every entry of the new beam carries its own p_b / p_nb
         lds_barrier();
         PHASE_MARK(6);
     }  // frames of the chunk
@@ -955,7 +984,7 @@ __global__ __launch_bounds__(kThreads) void beam_kernel(BeamArgs a) {
             a.out_scores[b] = -INFINITY;
         } else {
             a.out_lengths[b] = fin.plen[best];
-            a.out_scores[b] = (float)fin.ptot[best];
+            a.out_scores[b] = (float)(fin.ptot[best] + bias);
         }
         if (a.stats) {
             atomicAdd((unsigned long long*)&a.stats->frames, (unsigned long long)len);
@@ -1030,8 +1059,8 @@ __global__ __launch_bounds__(kThreads) void beam_kernel(BeamArgs a) {
             const int64_t row = (int64_t)b * beam + rank;
             const int n = fin.plen[tid];
             a.nbest_lengths[row] = n;
-            a.nbest_pb[row] = fin.pb[tid];
-            a.nbest_pnb[row] = fin.pnb[tid];
+            a.nbest_pb[row] = (collapsed ? fin.ptot[tid] : fin.pb[tid]) + bias;
+            a.nbest_pnb[row] = collapsed ? -INFINITY : fin.pnb[tid] + bias;
             int node = fin.node[tid];
             int32_t* dst = a.nbest_tokens + row * a.T;
             for (int p = n - 1; p >= 0 && node > 0 && (int64_t)node < a.trie_stride; --p) {

@@ -62,15 +62,21 @@ def load():
     lib.fltop_oracle_prefix_hash.argtypes = [i32p, ctypes.c_int32]
     lib.fltop_oracle_survivors.restype = ctypes.c_int
     lib.fltop_oracle_survivors.argtypes = [f32p, ctypes.c_int64, ctypes.c_int32, ctypes.c_float,
-                                           i32p, i32p, f32p]
+                                           ctypes.c_int32, i32p, i32p, f32p]
     lib.fltop_oracle_decode.restype = ctypes.c_int
     lib.fltop_oracle_decode.argtypes = [f32p, i32p, ctypes.c_int32, ctypes.c_int32,
-                                        ctypes.c_int32, ctypes.c_int32, ctypes.c_float, f32p,
+                                        ctypes.c_int32, ctypes.c_int32, ctypes.c_float,
+                                        ctypes.c_int32, ctypes.c_double, f32p,
                                         ctypes.c_float, ctypes.c_float, ctypes.c_int32, i32p,
-                                        i32p, f64p, ctypes.POINTER(OracleStats), ctypes.c_int32]
+                                        i32p, f64p, i32p, i32p, ctypes.POINTER(OracleStats),
+                                        ctypes.c_int32]
     lib.fltop_oracle_decode_beam.restype = ctypes.c_int
+    lib.fltop_oracle_token_ranks.restype = ctypes.c_int
+    lib.fltop_oracle_token_ranks.argtypes = [f32p, ctypes.c_int32, ctypes.c_int32, i32p, i32p,
+                                             ctypes.c_int32, i32p]
     lib.fltop_oracle_decode_beam.argtypes = [f32p, ctypes.c_int32, ctypes.c_int32,
-                                             ctypes.c_int32, ctypes.c_float, f32p,
+                                             ctypes.c_int32, ctypes.c_float, ctypes.c_int32,
+                                             ctypes.c_double, f32p,
                                              ctypes.c_float, ctypes.c_float, ctypes.c_int32,
                                              ctypes.c_int32, i32p, i32p, f64p, f64p]
     _lib = lib
@@ -92,7 +98,7 @@ def prefix_hash(tokens) -> int:
     return int(load().fltop_oracle_prefix_hash(ptr, arr.size))
 
 
-def survivors(logprobs: np.ndarray, rel_threshold: float):
+def survivors(logprobs: np.ndarray, rel_threshold: float, top_n: int = 0):
     """Per-frame survivor sets of [..., V] emissions -> (counts[F], tokens[F,V], frame_max[F])."""
     lp, lp_p = _f32(logprobs)
     V = lp.shape[-1]
@@ -101,7 +107,8 @@ def survivors(logprobs: np.ndarray, rel_threshold: float):
     tokens = np.full((F, V), -1, dtype=np.int32)
     fmax = np.zeros(F, dtype=np.float32)
     rc = load().fltop_oracle_survivors(
-        lp_p, F, V, float(rel_threshold), counts.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
+        lp_p, F, V, float(rel_threshold), int(top_n),
+        counts.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
         tokens.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
         fmax.ctypes.data_as(ctypes.POINTER(ctypes.c_float)))
     if rc != 0:
@@ -110,9 +117,15 @@ def survivors(logprobs: np.ndarray, rel_threshold: float):
 
 
 def decode(logprobs: np.ndarray, lengths: np.ndarray, beam: int, rel_threshold: float, *,
+           top_n: int = 0, beam_threshold: float = 0.0,
            lm_table: Optional[np.ndarray] = None, lm_weight: float = 0.0,
-           insertion_bonus: float = 0.0, variant: int = FLTOP, n_threads: int = 1):
-    """Best prefix per utterance -> (list of token lists, scores fp64 [B], stats dict)."""
+           insertion_bonus: float = 0.0, variant: int = FLTOP, n_threads: int = 1,
+           traces: bool = False):
+    """Best prefix per utterance -> (list of token lists, scores fp64 [B], stats dict).
+
+    With traces=True the stats dict also holds "token_frames" (list per utterance: frame at
+    which each output token's prefix entered the beam) and "frame_beam" ([B,T] int32, beam
+    entries kept after each frame, -1 beyond the utterance's length)."""
     lp, lp_p = _f32(logprobs)
     B, T, V = lp.shape
     ln, ln_p = _i32(lengths)
@@ -125,20 +138,44 @@ def decode(logprobs: np.ndarray, lengths: np.ndarray, beam: int, rel_threshold: 
     out_len = np.zeros(B, dtype=np.int32)
     out_sc = np.zeros(B, dtype=np.float64)
     st = OracleStats()
+    i32p = ctypes.POINTER(ctypes.c_int32)
+    tok_frames = np.full((B, max(T, 1)), -1, dtype=np.int32) if traces else None
+    frame_beam = np.full((B, max(T, 1)), -1, dtype=np.int32) if traces else None
     rc = load().fltop_oracle_decode(
-        lp_p, ln_p, B, T, V, int(beam), float(rel_threshold), lm_p, float(lm_weight),
-        float(insertion_bonus), int(variant),
-        out_tok.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
-        out_len.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
-        out_sc.ctypes.data_as(ctypes.POINTER(ctypes.c_double)), ctypes.byref(st),
+        lp_p, ln_p, B, T, V, int(beam), float(rel_threshold), int(top_n), float(beam_threshold),
+        lm_p, float(lm_weight), float(insertion_bonus), int(variant),
+        out_tok.ctypes.data_as(i32p), out_len.ctypes.data_as(i32p),
+        out_sc.ctypes.data_as(ctypes.POINTER(ctypes.c_double)),
+        tok_frames.ctypes.data_as(i32p) if traces else None,
+        frame_beam.ctypes.data_as(i32p) if traces else None, ctypes.byref(st),
         int(n_threads))
     if rc != 0:
         raise ValueError("fltop_oracle_decode: bad arguments")
     toks = [out_tok[b, :out_len[b]].tolist() for b in range(B)]
-    return toks, out_sc, st.as_dict()
+    stats = st.as_dict()
+    if traces:
+        stats["token_frames"] = [tok_frames[b, :out_len[b]].tolist() for b in range(B)]
+        stats["frame_beam"] = frame_beam[:, :T]
+    return toks, out_sc, stats
+
+
+def token_ranks(logprobs: np.ndarray, tokens, frames) -> np.ndarray:
+    """Position of tokens[i] in the descending sort of frame frames[i] of one [T,V] utterance."""
+    lp, lp_p = _f32(logprobs)
+    T, V = lp.shape
+    tk, tk_p = _i32(np.asarray(tokens, dtype=np.int32).reshape(-1))
+    fr, fr_p = _i32(np.asarray(frames, dtype=np.int32).reshape(-1))
+    assert tk.size == fr.size
+    ranks = np.zeros(tk.size, dtype=np.int32)
+    rc = load().fltop_oracle_token_ranks(lp_p, T, V, tk_p, fr_p, tk.size,
+                                         ranks.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)))
+    if rc != 0:
+        raise ValueError("fltop_oracle_token_ranks: bad arguments")
+    return ranks
 
 
 def decode_beam(logprobs: np.ndarray, beam: int, rel_threshold: float, *,
+                top_n: int = 0, beam_threshold: float = 0.0,
                 lm_table: Optional[np.ndarray] = None, lm_weight: float = 0.0,
                 insertion_bonus: float = 0.0, variant: int = FLTOP, max_entries: int = 0):
     """Whole final beam of one [T,V] utterance -> list of (tokens tuple, p_b, p_nb) in rank order."""
@@ -155,8 +192,8 @@ def decode_beam(logprobs: np.ndarray, beam: int, rel_threshold: float, *,
     pb = np.zeros(cap, dtype=np.float64)
     pnb = np.zeros(cap, dtype=np.float64)
     n = load().fltop_oracle_decode_beam(
-        lp_p, T, V, int(beam), float(rel_threshold), lm_p, float(lm_weight),
-        float(insertion_bonus), int(variant), cap,
+        lp_p, T, V, int(beam), float(rel_threshold), int(top_n), float(beam_threshold), lm_p,
+        float(lm_weight), float(insertion_bonus), int(variant), cap,
         toks.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
         lens.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
         pb.ctypes.data_as(ctypes.POINTER(ctypes.c_double)),

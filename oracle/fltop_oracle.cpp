@@ -71,15 +71,36 @@ float ln_r_fp32(float r) {
     return (float)std::log((double)r);
 }
 
-void frame_survivors(const float* row, int32_t V, float ln_r, std::vector<int32_t>& S,
-                     float* top) {
-    float m = row[0];
-    for (int32_t v = 1; v < V; ++v)
-        if (row[v] > m) m = row[v];
+struct EmissionBefore { /* descending emission, equal emissions by ascending token id */
+    const float* row;
+    bool operator()(int32_t a, int32_t b) const {
+        if (row[a] != row[b]) return row[a] > row[b];
+        return a < b;
+    }
+};
+
+/* Alg. 1 in its printed order: partial sort of the frame to its N best tokens, the top
+ * emission is the first of them, then walk down the sorted list and stop at the first
+ * token that fails the relative-threshold test.  top_n <= 0 or >= V: all V tokens enter
+ * the walk.  S is returned in ascending token order (the expansion is a set union, so
+ * the order in which survivors are visited does not matter). */
+void frame_survivors(const float* row, int32_t V, int32_t top_n, float ln_r,
+                     std::vector<int32_t>& S, float* top) {
+    const int32_t n = (top_n <= 0 || top_n > V) ? V : top_n;
+    std::vector<int32_t> sorted_idx(V);
+    for (int32_t v = 0; v < V; ++v) sorted_idx[v] = v;
+    EmissionBefore before;
+    before.row = row;
+    std::partial_sort(sorted_idx.begin(), sorted_idx.begin() + n, sorted_idx.end(), before);
+    const float m = row[sorted_idx[0]];
     volatile float thr = m + ln_r; /* one fp32 add; volatile keeps it in fp32 */
     S.clear();
-    for (int32_t v = 0; v < V; ++v)
-        if (row[v] >= thr) S.push_back(v);
+    for (int32_t i = 0; i < n; ++i) {
+        const int32_t v = sorted_idx[i];
+        if (!(row[v] >= thr)) break;
+        S.push_back(v);
+    }
+    std::sort(S.begin(), S.end());
     if (top) *top = m;
 }
 
@@ -87,6 +108,9 @@ void frame_survivors(const float* row, int32_t V, float ln_r, std::vector<int32_
 struct Mass {
     double pb, pnb;
     int32_t terms_b, terms_nb;
+    /* born[i] = frame at which the prefix of length i+1 entered the beam on the way to this
+     * entry (statistics only; plays no part in the search) */
+    std::vector<int32_t> born;
     Mass() : pb(NEG_INF), pnb(NEG_INF), terms_b(0), terms_nb(0) {}
     double total() const { return log_add(pb, pnb); }
 };
@@ -114,9 +138,10 @@ struct LocalStats {
           min_cut_margin(std::numeric_limits<double>::infinity()) {}
 };
 
-/* Rank the live candidates of `next` (score desc, hash asc), record statistics,
- * and return the best `beam` of them as the new beam. */
-Beam keep_best(const Beam& next, int32_t beam, LocalStats& st) {
+/* SelectTopK of Alg. 1: rank the live candidates of `next` (score desc, hash asc), drop
+ * those whose score lies more than `beam_threshold` below the best one (when that
+ * window is switched on, i.e. > 0), and return the best `beam` of the rest. */
+Beam keep_best(const Beam& next, int32_t beam, double beam_threshold, LocalStats& st) {
     std::vector<Ranked> order;
     for (Beam::const_iterator it = next.begin(); it != next.end(); ++it) {
         double tot = it->second.total();
@@ -135,6 +160,13 @@ Beam keep_best(const Beam& next, int32_t beam, LocalStats& st) {
     int64_t n = (int64_t)order.size();
     st.sum_candidates += n;
     if (n > st.peak_candidates) st.peak_candidates = n;
+    if (beam_threshold > 0.0 && n > 0) {
+        const double floor_score = order[0].total - beam_threshold;
+        size_t inside = 0;
+        while (inside < order.size() && order[inside].total >= floor_score) ++inside;
+        order.resize(inside); /* the list is sorted, so the window is a leading run */
+        n = (int64_t)order.size();
+    }
     if (n > beam) {
         double margin = order[beam - 1].total - order[beam].total;
         if (margin < st.min_cut_margin) st.min_cut_margin = margin;
@@ -160,10 +192,31 @@ std::vector<Ranked> rank_all(const Beam& b) {
     return order;
 }
 
+/* What Alg. 1 takes besides the emissions and the LM. */
+struct SearchSpec {
+    int32_t beam;          /* beam_size */
+    float rel_threshold;   /* R */
+    int32_t top_n;         /* N; <= 0: all tokens */
+    double beam_threshold; /* score window of SelectTopK; <= 0: off */
+    int32_t* frame_beam;   /* NULL or [len]: entries kept after each frame (statistics) */
+};
+
+/* A candidate that is not in the current beam is a prefix that enters now. */
+void note_birth(Mass& fresh, const Beam& cur, const Prefix& ext, const Mass& parent, int32_t t) {
+    if (!fresh.born.empty() || ext.empty()) return;
+    Beam::const_iterator old = cur.find(ext);
+    if (old != cur.end()) {
+        fresh.born = old->second.born;
+    } else {
+        fresh.born = parent.born;
+        fresh.born.push_back(t);
+    }
+}
+
 /* ---- Algorithm 1 (FLToP) --------------------------------------------------------- */
-Beam decode_fltop(const float* lp, int32_t len, int32_t V, int32_t beam, float rel_threshold,
+Beam decode_fltop(const float* lp, int32_t len, int32_t V, const SearchSpec& spec,
                   const LmSpec& lm, LocalStats& st) {
-    const float ln_r = ln_r_fp32(rel_threshold);
+    const float ln_r = ln_r_fp32(spec.rel_threshold);
     Beam cur;
     Mass start;
     start.pb = 0.0; /* the empty prefix with score 0 */
@@ -171,7 +224,7 @@ Beam decode_fltop(const float* lp, int32_t len, int32_t V, int32_t beam, float r
     std::vector<int32_t> S;
     for (int32_t t = 0; t < len; ++t) {
         const float* row = lp + (int64_t)t * V;
-        frame_survivors(row, V, ln_r, S, 0);
+        frame_survivors(row, V, spec.top_n, ln_r, S, 0);
         st.frames++;
         st.sum_survivors += (int64_t)S.size();
         Beam next;
@@ -188,27 +241,32 @@ Beam decode_fltop(const float* lp, int32_t len, int32_t V, int32_t beam, float r
                     Mass& d = next[prefix];
                     d.pb = log_add(d.pb, p_tot + x);
                     d.terms_b++;
+                    d.born = m.born;
                 } else if (s == last) {
                     /* repeat of the last token: collapses onto the same prefix ... */
                     Mass& d = next[prefix];
                     d.pnb = log_add(d.pnb, m.pnb + x);
                     d.terms_nb++;
+                    d.born = m.born;
                     /* ... unless a blank separated them: then it is a new token */
                     Prefix ext(prefix);
                     ext.push_back(s);
                     Mass& e = next[ext];
                     e.pnb = log_add(e.pnb, m.pb + x + lm.term(last, s));
                     e.terms_nb++;
+                    note_birth(e, cur, ext, m, t);
                 } else {
                     Prefix ext(prefix);
                     ext.push_back(s);
                     Mass& e = next[ext];
                     e.pnb = log_add(e.pnb, p_tot + x + lm.term(last, s));
                     e.terms_nb++;
+                    note_birth(e, cur, ext, m, t);
                 }
             }
         }
-        cur = keep_best(next, beam, st);
+        cur = keep_best(next, spec.beam, spec.beam_threshold, st);
+        if (spec.frame_beam) spec.frame_beam[t] = (int32_t)cur.size();
     }
     return cur;
 }
@@ -301,16 +359,20 @@ Beam decode_textbook(const float* lp, int32_t len, int32_t V, int32_t beam, cons
     return out;
 }
 
-Beam decode_one(const float* lp, int32_t len, int32_t V, int32_t beam, float r, const LmSpec& lm,
+Beam decode_one(const float* lp, int32_t len, int32_t V, const SearchSpec& spec, const LmSpec& lm,
                 int32_t variant, LocalStats& st) {
-    if (variant == FLTOP_ORACLE_TEXTBOOK) return decode_textbook(lp, len, V, beam, lm, st);
-    return decode_fltop(lp, len, V, beam, r, lm, st);
+    if (variant == FLTOP_ORACLE_TEXTBOOK) return decode_textbook(lp, len, V, spec.beam, lm, st);
+    return decode_fltop(lp, len, V, spec, lm, st);
 }
 
-bool bad_common(const void* lp, int32_t T, int32_t V, int32_t beam, float r, int32_t variant) {
+bool bad_common(const void* lp, int32_t T, int32_t V, int32_t beam, float r, int32_t top_n,
+                double beam_threshold, int32_t variant) {
     if (!lp || T < 0 || V < 1 || beam < 1) return true;
     if (!(r >= 0.0f && r <= 1.0f)) return true; /* also rejects NaN */
+    if (top_n < 0 || beam_threshold != beam_threshold) return true;
     if (variant != FLTOP_ORACLE_FLTOP && variant != FLTOP_ORACLE_TEXTBOOK) return true;
+    /* the classic search has neither a token stage nor a score window */
+    if (variant == FLTOP_ORACLE_TEXTBOOK && (top_n > 0 || beam_threshold > 0.0)) return true;
     return false;
 }
 
@@ -323,15 +385,15 @@ extern "C" uint64_t fltop_oracle_prefix_hash(const int32_t* tokens, int32_t n) {
 }
 
 extern "C" int fltop_oracle_survivors(const float* logprobs, int64_t n_frames, int32_t V,
-                                      float rel_threshold, int32_t* counts, int32_t* tokens,
-                                      float* frame_max) {
-    if (!logprobs || !counts || !tokens || n_frames < 0 || V < 1) return -1;
+                                      float rel_threshold, int32_t top_n, int32_t* counts,
+                                      int32_t* tokens, float* frame_max) {
+    if (!logprobs || !counts || !tokens || n_frames < 0 || V < 1 || top_n < 0) return -1;
     if (!(rel_threshold >= 0.0f && rel_threshold <= 1.0f)) return -1;
     const float ln_r = ln_r_fp32(rel_threshold);
     std::vector<int32_t> S;
     for (int64_t f = 0; f < n_frames; ++f) {
         float top;
-        frame_survivors(logprobs + f * V, V, ln_r, S, &top);
+        frame_survivors(logprobs + f * V, V, top_n, ln_r, S, &top);
         counts[f] = (int32_t)S.size();
         for (size_t k = 0; k < S.size(); ++k) tokens[f * V + (int64_t)k] = S[k];
         if (frame_max) frame_max[f] = top;
@@ -341,11 +403,14 @@ extern "C" int fltop_oracle_survivors(const float* logprobs, int64_t n_frames, i
 
 extern "C" int fltop_oracle_decode(const float* logprobs, const int32_t* lengths, int32_t B,
                                    int32_t T, int32_t V, int32_t beam, float rel_threshold,
-                                   const float* lm_table, float lm_weight, float insertion_bonus,
-                                   int32_t variant, int32_t* out_tokens, int32_t* out_lengths,
-                                   double* out_scores, fltop_oracle_stats* stats,
-                                   int32_t n_threads) {
-    if (bad_common(logprobs, T, V, beam, rel_threshold, variant)) return -1;
+                                   int32_t top_n, double beam_threshold, const float* lm_table,
+                                   float lm_weight, float insertion_bonus, int32_t variant,
+                                   int32_t* out_tokens, int32_t* out_lengths, double* out_scores,
+                                   int32_t* out_token_frames, int32_t* frame_beam,
+                                   fltop_oracle_stats* stats, int32_t n_threads) {
+    if (bad_common(logprobs, T, V, beam, rel_threshold, top_n, beam_threshold, variant))
+        return -1;
+    if (variant == FLTOP_ORACLE_TEXTBOOK && (out_token_frames || frame_beam)) return -1;
     if (!lengths || B < 0 || !out_tokens || !out_lengths || !out_scores || n_threads < 1)
         return -1;
     for (int32_t b = 0; b < B; ++b)
@@ -364,8 +429,14 @@ extern "C" int fltop_oracle_decode(const float* logprobs, const int32_t* lengths
         for (;;) {
             int32_t b = next_utt.fetch_add(1);
             if (b >= B) break;
-            Beam fin = decode_one(logprobs + (int64_t)b * T * V, lengths[b], V, beam,
-                                  rel_threshold, lm, variant, mine);
+            SearchSpec spec;
+            spec.beam = beam;
+            spec.rel_threshold = rel_threshold;
+            spec.top_n = top_n;
+            spec.beam_threshold = beam_threshold;
+            spec.frame_beam = frame_beam ? frame_beam + (int64_t)b * T : 0;
+            Beam fin = decode_one(logprobs + (int64_t)b * T * V, lengths[b], V, spec, lm, variant,
+                                  mine);
             std::vector<Ranked> order = rank_all(fin);
             int32_t* dst = out_tokens + (int64_t)b * T;
             if (order.empty()) { /* every route died (a frame of all -inf) */
@@ -377,6 +448,11 @@ extern "C" int fltop_oracle_decode(const float* logprobs, const int32_t* lengths
             out_lengths[b] = (int32_t)best.size();
             for (size_t i = 0; i < best.size(); ++i) dst[i] = best[i];
             out_scores[b] = order[0].total;
+            if (out_token_frames) {
+                const std::vector<int32_t>& born = order[0].it->second.born;
+                for (size_t i = 0; i < born.size(); ++i)
+                    out_token_frames[(int64_t)b * T + (int64_t)i] = born[i];
+            }
         }
         std::lock_guard<std::mutex> g(merge_lock);
         all.frames += mine.frames;
@@ -407,12 +483,14 @@ extern "C" int fltop_oracle_decode(const float* logprobs, const int32_t* lengths
 }
 
 extern "C" int fltop_oracle_decode_beam(const float* logprobs, int32_t T, int32_t V, int32_t beam,
-                                        float rel_threshold, const float* lm_table,
+                                        float rel_threshold, int32_t top_n,
+                                        double beam_threshold, const float* lm_table,
                                         float lm_weight, float insertion_bonus, int32_t variant,
                                         int32_t max_entries, int32_t* beam_tokens,
                                         int32_t* beam_lengths, double* beam_pb,
                                         double* beam_pnb) {
-    if (bad_common(logprobs, T, V, beam, rel_threshold, variant)) return -1;
+    if (bad_common(logprobs, T, V, beam, rel_threshold, top_n, beam_threshold, variant))
+        return -1;
     if (max_entries < 0 || !beam_tokens || !beam_lengths || !beam_pb || !beam_pnb) return -1;
     LmSpec lm;
     lm.table = lm_table;
@@ -420,7 +498,13 @@ extern "C" int fltop_oracle_decode_beam(const float* logprobs, int32_t T, int32_
     lm.alpha = (double)lm_weight;
     lm.beta = (double)insertion_bonus;
     LocalStats st;
-    Beam fin = decode_one(logprobs, T, V, beam, rel_threshold, lm, variant, st);
+    SearchSpec spec;
+    spec.beam = beam;
+    spec.rel_threshold = rel_threshold;
+    spec.top_n = top_n;
+    spec.beam_threshold = beam_threshold;
+    spec.frame_beam = 0;
+    Beam fin = decode_one(logprobs, T, V, spec, lm, variant, st);
     std::vector<Ranked> order = rank_all(fin);
     int32_t n = (int32_t)std::min<size_t>(order.size(), (size_t)max_entries);
     for (int32_t i = 0; i < n; ++i) {
@@ -431,4 +515,22 @@ extern "C" int fltop_oracle_decode_beam(const float* logprobs, int32_t T, int32_
         beam_pnb[i] = order[i].it->second.pnb;
     }
     return n;
+}
+
+extern "C" int fltop_oracle_token_ranks(const float* logprobs, int32_t T, int32_t V,
+                                        const int32_t* tokens, const int32_t* frames, int32_t n,
+                                        int32_t* ranks) {
+    if (!logprobs || T < 0 || V < 1 || n < 0 || (n > 0 && (!tokens || !frames || !ranks)))
+        return -1;
+    for (int32_t i = 0; i < n; ++i) {
+        if (frames[i] < 0 || frames[i] >= T || tokens[i] < 0 || tokens[i] >= V) return -1;
+        const float* row = logprobs + (int64_t)frames[i] * V;
+        EmissionBefore before;
+        before.row = row;
+        int32_t ahead = 0; /* tokens that the descending sort of the frame puts first */
+        for (int32_t v = 0; v < V; ++v)
+            if (v != tokens[i] && before(v, tokens[i])) ++ahead;
+        ranks[i] = ahead;
+    }
+    return 0;
 }

@@ -56,24 +56,34 @@ uint64_t fltop_oracle_prefix_hash(const int32_t* tokens, int32_t n);
 /* Per-frame survivor sets (Alg. 1, the relative-threshold test, read in the
  * probability domain): token v survives iff lp[v] >= max_v lp[v] + ln(r), the
  * sum taken as one fp32 addition of fp32 operands, ln(r) rounded to fp32 once
- * (r = 0 gives -inf).  counts[f] = |S_f|; tokens[f*V .. f*V+counts[f]) ascending;
- * frame_max[f] = the top emission.  Returns 0, or -1 on bad arguments. */
+ * (r = 0 gives -inf).  With top_n > 0 only the N best tokens of the frame (Alg. 1's
+ * partial sort; equal emissions ordered by ascending token id) take the test at all.
+ * counts[f] = |S_f|; tokens[f*V .. f*V+counts[f]) ascending; frame_max[f] = the top
+ * emission.  Returns 0, or -1 on bad arguments. */
 int fltop_oracle_survivors(const float* logprobs, int64_t n_frames, int32_t V,
-                           float rel_threshold, int32_t* counts, int32_t* tokens,
-                           float* frame_max);
+                           float rel_threshold, int32_t top_n, int32_t* counts,
+                           int32_t* tokens, float* frame_max);
 
 /* Batch decode, best prefix per utterance.
  *  logprobs [B,T,V] fp32, lengths [B] (frames >= lengths[b] are never read),
+ *  top_n: Alg. 1's N (0 = all tokens), beam_threshold: SelectTopK's score window --
+ *  candidates scoring more than this below the frame's best one are dropped before the
+ *  top-`beam` cut (<= 0 = no window),
  *  lm_table NULL or [V,V] fp32 log-probs (row = previous token, row 0 for the
  *  first token; applied as lm_weight*table + insertion_bonus on every extension),
  *  out_tokens [B,T], out_lengths [B], out_scores [B] (fp64),
+ *  out_token_frames NULL or [B,T]: for token i of the best prefix, the frame at which
+ *  the prefix of length i+1 entered the beam (on the lineage of the final entry),
+ *  frame_beam NULL or [B,T]: number of beam entries kept after each frame,
  *  stats NULL or one struct accumulated over the batch, n_threads >= 1.
+ * The TEXTBOOK variant takes neither top_n, beam_threshold nor the two traces.
  * Returns 0, or -1 on bad arguments. */
 int fltop_oracle_decode(const float* logprobs, const int32_t* lengths,
                         int32_t B, int32_t T, int32_t V, int32_t beam,
-                        float rel_threshold, const float* lm_table,
-                        float lm_weight, float insertion_bonus, int32_t variant,
-                        int32_t* out_tokens, int32_t* out_lengths, double* out_scores,
+                        float rel_threshold, int32_t top_n, double beam_threshold,
+                        const float* lm_table, float lm_weight, float insertion_bonus,
+                        int32_t variant, int32_t* out_tokens, int32_t* out_lengths,
+                        double* out_scores, int32_t* out_token_frames, int32_t* frame_beam,
                         fltop_oracle_stats* stats, int32_t n_threads);
 
 /* Single utterance, whole final beam in rank order (score desc, hash asc).
@@ -81,10 +91,18 @@ int fltop_oracle_decode(const float* logprobs, const int32_t* lengths,
  *  [max_entries].  Returns the number of entries written (<= max_entries), or
  *  -1 on bad arguments. */
 int fltop_oracle_decode_beam(const float* logprobs, int32_t T, int32_t V, int32_t beam,
-                             float rel_threshold, const float* lm_table,
+                             float rel_threshold, int32_t top_n, double beam_threshold,
+                             const float* lm_table,
                              float lm_weight, float insertion_bonus, int32_t variant,
                              int32_t max_entries, int32_t* beam_tokens,
                              int32_t* beam_lengths, double* beam_pb, double* beam_pnb);
+
+/* Position of tokens[i] in the descending sort of frame frames[i] of one [T,V] utterance
+ * (0 = the top emission; equal emissions by ascending token id): the "index of the chosen
+ * token" statistic of the paper's Sec. 4.1.  Returns 0, or -1 on bad arguments. */
+int fltop_oracle_token_ranks(const float* logprobs, int32_t T, int32_t V,
+                             const int32_t* tokens, const int32_t* frames, int32_t n,
+                             int32_t* ranks);
 
 #ifdef __cplusplus
 }

@@ -8,8 +8,12 @@
  *   beam <- { (empty prefix, score 0) }
  *   for each frame t < length:
  *       S_t  <- { v : lp[t][v] >= max_v lp[t][v] + ln R }      (relative threshold)
+ *               restricted, if N is given, to the N best tokens of the frame
+ *               (PartialSortDesc; equal emissions in ascending token order)
  *       expand every beam entry by every token of S_t           (blank / repeat / extend)
- *       merge equal prefixes (log-sum-exp), keep the best `beam` (SelectTopK)
+ *       merge equal prefixes (log-sum-exp),
+ *       drop what scores more than beam_threshold below the frame's best candidate
+ *       (if that window is given), keep the best `beam`         (SelectTopK)
  *   return the best prefix                                      (GetHighestScorePrefix)
  *
  * Algorithm 1 leaves the CTC collapse abstract ("prefix + token", "score +
@@ -55,17 +59,23 @@ extern "C" {
 #define FLTOP_ERR_VOCAB_TOO_BIG  -6  /* V > FLTOP_MAX_VOCAB                                 */
 #define FLTOP_ERR_HIP            -7  /* a HIP call or kernel launch failed                  */
 #define FLTOP_ERR_ALIGNMENT      -8  /* workspace not 256-byte aligned                      */
+#define FLTOP_ERR_BAD_OPTION     -9  /* top_n < 0, or beam_threshold NaN                    */
 
 #define FLTOP_MAX_BEAM   128
 #define FLTOP_MAX_VOCAB  4096
 
-/* Decoder settings (host POD, read during the call only).
- * Algorithm 1's arguments: beam_size -> beam, R -> rel_threshold, LM -> the
- * three lm fields.  Its N (static top-N stage) is V here and its
- * beam_threshold is not applied. */
+/* Decoder settings (host POD, read during the call only; zero-initialise it, then set
+ * what is needed).  Algorithm 1's arguments: beam_size -> beam, R -> rel_threshold,
+ * N -> top_n, beam_threshold -> beam_threshold, LM -> the three lm fields. */
 typedef struct fltop_params {
     int32_t      beam;             /* 1 .. FLTOP_MAX_BEAM                                       */
     float        rel_threshold;    /* R in [0,1]; 0 keeps every token (unpruned search)         */
+    int32_t      top_n;            /* N: only the N best tokens of a frame take the threshold
+                                      test; 0 (or >= V) = all tokens                            */
+    int32_t      reserved;         /* set to 0                                                  */
+    double       beam_threshold;   /* SelectTopK's score window: candidates scoring more than
+                                      this below the frame's best candidate are dropped before
+                                      the top-`beam` cut; <= 0 = no window                      */
     const float* lm_table;         /* dev [V,V] fp32 log-probs, row = previous token (row 0 for
                                       the first token of a prefix), or NULL for no LM           */
     float        lm_weight;        /* extension adds lm_weight * lm_table[prev][tok]            */
@@ -76,6 +86,11 @@ typedef struct fltop_params {
     int32_t*     nbest_lengths;    /* dev [B,beam]                                              */
     double*      nbest_pb;         /* dev [B,beam]     log-mass ending in blank                 */
     double*      nbest_pnb;        /* dev [B,beam]     log-mass ending in the last token        */
+    /* Optional statistics traces (paper Sec. 4.1 and 4.4; each NULL to skip).                 */
+    int32_t*     frame_beam;       /* dev [B,T]  beam entries kept after frame t (valid frames
+                                      only, rest untouched): hypotheses per time step           */
+    int32_t*     out_token_frames; /* dev [B,T]  for token i of the returned prefix, the frame at
+                                      which the prefix of length i+1 entered the beam           */
 } fltop_params;
 
 /* Counters accumulated (added to) by fltop_ctc_decode; zero them beforehand. */
@@ -121,19 +136,19 @@ int fltop_ctc_decode(const float* logprobs, const int32_t* lengths,
 
 /* The first stage alone (Algorithm 1's top-emission lookup and relative-
  * threshold test, which do not depend on the hypotheses, for every valid frame
- * at once): writes the survivor lists into `workspace` in the library's
- * internal layout.  Same argument rules as fltop_ctc_decode (`beam` only sizes
- * the workspace check). */
+ * at once, preceded by the static top-N stage when top_n > 0): writes the
+ * survivor lists into `workspace` in the library's internal layout.  Same
+ * argument rules as fltop_ctc_decode (`beam` only sizes the workspace check). */
 int fltop_ctc_prune(const float* logprobs, const int32_t* lengths,
                     int32_t B, int32_t T, int32_t V, int32_t beam, float rel_threshold,
-                    void* workspace, size_t workspace_bytes, void* hip_stream);
+                    int32_t top_n, void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* The second stage alone (Algorithm 1's loop over beam entries and kept tokens,
  * SelectTopK and GetHighestScorePrefix) over survivor lists that fltop_ctc_prune
  * left in `workspace` for the same logprobs, lengths, shapes and beam.
  * fltop_ctc_decode is exactly fltop_ctc_prune followed by this call; the split
  * exists so that each stage can be timed and tested by itself.  Argument rules as
- * for fltop_ctc_decode; params->rel_threshold is not used here. */
+ * for fltop_ctc_decode; params->rel_threshold and params->top_n are not used here. */
 int fltop_ctc_search(const int32_t* lengths, int32_t B, int32_t T, int32_t V,
                      const fltop_params* params, void* workspace, size_t workspace_bytes,
                      int32_t* out_tokens, int32_t* out_lengths, float* out_scores,
@@ -149,6 +164,20 @@ int fltop_ctc_unpack_survivors(const void* workspace, size_t workspace_bytes,
                                const int32_t* lengths, int32_t B, int32_t T, int32_t V,
                                int32_t beam, int32_t* counts, int32_t* tokens, float* values,
                                float* frame_max, void* hip_stream);
+
+/* "Index of the chosen token" statistic (paper Sec. 4.1): for every token i of the
+ * returned prefixes, its position in the descending sort of the emissions of the frame
+ * out_token_frames[b][i] (0 = top emission; equal emissions in ascending token order).
+ *   tokens, token_frames  dev [B,T] as written by fltop_ctc_decode (out_tokens and
+ *                         params->out_token_frames), token_counts dev [B] (out_lengths)
+ *   out_ranks   dev [B,T] int32, first token_counts[b] entries of row b, or NULL
+ *   rank_count  dev [V] uint64, rank_count[k] += tokens chosen at position k, or NULL
+ *   rank_lp_sum dev [V] fp64,   rank_lp_sum[k] += their log-probabilities (the order of
+ *               the additions is not fixed), or NULL; zero both beforehand. */
+int fltop_ctc_token_ranks(const float* logprobs, int32_t B, int32_t T, int32_t V,
+                          const int32_t* tokens, const int32_t* token_frames,
+                          const int32_t* token_counts, int32_t* out_ranks,
+                          uint64_t* rank_count, double* rank_lp_sum, void* hip_stream);
 
 /* Human-readable name of a status code (static storage). */
 const char* fltop_status_string(int status);

@@ -19,13 +19,16 @@ MAX_BEAM = 128
 MAX_VOCAB = 4096
 
 EXPORTS = ("fltop_ctc_workspace_bytes", "fltop_ctc_decode", "fltop_ctc_prune", "fltop_ctc_search",
-           "fltop_ctc_unpack_survivors", "fltop_status_string")
+           "fltop_ctc_unpack_survivors", "fltop_ctc_token_ranks", "fltop_status_string")
 
 
 class FltopParams(ctypes.Structure):
     _fields_ = [
         ("beam", ctypes.c_int32),
         ("rel_threshold", ctypes.c_float),
+        ("top_n", ctypes.c_int32),
+        ("reserved", ctypes.c_int32),
+        ("beam_threshold", ctypes.c_double),
         ("lm_table", ctypes.c_void_p),
         ("lm_weight", ctypes.c_float),
         ("insertion_bonus", ctypes.c_float),
@@ -34,6 +37,8 @@ class FltopParams(ctypes.Structure):
         ("nbest_lengths", ctypes.c_void_p),
         ("nbest_pb", ctypes.c_void_p),
         ("nbest_pnb", ctypes.c_void_p),
+        ("frame_beam", ctypes.c_void_p),
+        ("out_token_frames", ctypes.c_void_p),
     ]
 
 
@@ -69,7 +74,9 @@ def load():
     lib.fltop_ctc_search.argtypes = [vp, i32, i32, i32, ctypes.POINTER(FltopParams), vp, sz,
                                      vp, vp, vp, vp, vp]
     lib.fltop_ctc_prune.restype = ctypes.c_int
-    lib.fltop_ctc_prune.argtypes = [vp, vp, i32, i32, i32, i32, f32, vp, sz, vp]
+    lib.fltop_ctc_prune.argtypes = [vp, vp, i32, i32, i32, i32, f32, i32, vp, sz, vp]
+    lib.fltop_ctc_token_ranks.restype = ctypes.c_int
+    lib.fltop_ctc_token_ranks.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]
     lib.fltop_ctc_unpack_survivors.restype = ctypes.c_int
     lib.fltop_ctc_unpack_survivors.argtypes = [vp, sz, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp]
     lib.fltop_status_string.restype = ctypes.c_char_p
@@ -135,21 +142,24 @@ def search_raw(lengths, shape, params: FltopParams, workspace, workspace_nbytes,
 
 
 def prune_raw(logprobs, lengths, beam, rel_threshold, workspace, workspace_nbytes,
-              stream=None) -> int:
+              stream=None, top_n: int = 0) -> int:
     """Direct call of fltop_ctc_prune; returns the status code."""
     B, T, V = logprobs.shape
     return int(load().fltop_ctc_prune(_ptr(logprobs), _ptr(lengths), B, T, V, int(beam),
-                                      float(rel_threshold), _ptr(workspace), workspace_nbytes,
-                                      _stream_handle(stream)))
+                                      float(rel_threshold), int(top_n), _ptr(workspace),
+                                      workspace_nbytes, _stream_handle(stream)))
 
 
 def decode(logprobs: torch.Tensor, lengths: torch.Tensor, beam: int, rel_threshold: float, *,
+           top_n: int = 0, beam_threshold: float = 0.0,
            lm_table: Optional[torch.Tensor] = None, lm_weight: float = 0.0,
            insertion_bonus: float = 0.0, workspace: Optional[torch.Tensor] = None,
-           want_stats: bool = False, want_nbest: bool = False, stream=None) -> dict:
+           want_stats: bool = False, want_nbest: bool = False, want_traces: bool = False,
+           stream=None) -> dict:
     """fltop_ctc_decode on device tensors.  Returns device tensors (no host sync):
     tokens [B,T] int32, lengths [B] int32, scores [B] fp32, and optionally stats
-    (uint64 [8], see STATS_FIELDS) and the n-best export."""
+    (uint64 [8], see STATS_FIELDS), the n-best export, and the statistics traces
+    (frame_beam [B,T], token_frames [B,T], both int32 and -1 where nothing was written)."""
     _check_inputs(logprobs, lengths)
     B, T, V = logprobs.shape
     dev = logprobs.device
@@ -163,6 +173,8 @@ def decode(logprobs: torch.Tensor, lengths: torch.Tensor, beam: int, rel_thresho
     p = FltopParams()
     p.beam = int(beam)
     p.rel_threshold = float(rel_threshold)
+    p.top_n = int(top_n)
+    p.beam_threshold = float(beam_threshold)
     p.lm_weight = float(lm_weight)
     p.insertion_bonus = float(insertion_bonus)
     if lm_table is not None:
@@ -181,6 +193,11 @@ def decode(logprobs: torch.Tensor, lengths: torch.Tensor, beam: int, rel_thresho
         p.nbest_lengths = out["nbest_lengths"].data_ptr()
         p.nbest_pb = out["nbest_pb"].data_ptr()
         p.nbest_pnb = out["nbest_pnb"].data_ptr()
+    if want_traces:
+        out["frame_beam"] = torch.full((B, T), -1, dtype=torch.int32, device=dev)
+        out["token_frames"] = torch.full((B, T), -1, dtype=torch.int32, device=dev)
+        p.frame_beam = out["frame_beam"].data_ptr()
+        p.out_token_frames = out["token_frames"].data_ptr()
     stats = None
     if want_stats:
         stats = torch.zeros(len(STATS_FIELDS), dtype=torch.int64, device=dev)
@@ -194,15 +211,15 @@ def decode(logprobs: torch.Tensor, lengths: torch.Tensor, beam: int, rel_thresho
 
 
 def prune(logprobs: torch.Tensor, lengths: torch.Tensor, beam: int, rel_threshold: float, *,
-          workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+          top_n: int = 0, workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
     """fltop_ctc_prune: survivor lists into the workspace (returned)."""
     _check_inputs(logprobs, lengths)
     B, T, V = logprobs.shape
     if workspace is None:
         workspace = alloc_workspace(B, T, V, beam, logprobs.device)
     rc = int(load().fltop_ctc_prune(_ptr(logprobs), _ptr(lengths), B, T, V, int(beam),
-                                    float(rel_threshold), _ptr(workspace), workspace.numel(),
-                                    _stream_handle(stream)))
+                                    float(rel_threshold), int(top_n), _ptr(workspace),
+                                    workspace.numel(), _stream_handle(stream)))
     if rc != 0:
         raise FltopError(rc, "fltop_ctc_prune")
     return workspace
@@ -223,6 +240,23 @@ def unpack_survivors(workspace: torch.Tensor, lengths: torch.Tensor, B: int, T: 
     if rc != 0:
         raise FltopError(rc, "fltop_ctc_unpack_survivors")
     return counts, tokens, values, fmax
+
+
+def token_ranks(logprobs: torch.Tensor, tokens: torch.Tensor, token_frames: torch.Tensor,
+                token_counts: torch.Tensor, stream=None):
+    """fltop_ctc_token_ranks -> (ranks [B,T] int32 (-1 where unused), rank_count [V] int64,
+    rank_lp_sum [V] float64)."""
+    B, T, V = logprobs.shape
+    dev = logprobs.device
+    ranks = torch.full((B, T), -1, dtype=torch.int32, device=dev)
+    count = torch.zeros(V, dtype=torch.int64, device=dev)
+    lp_sum = torch.zeros(V, dtype=torch.float64, device=dev)
+    rc = int(load().fltop_ctc_token_ranks(_ptr(logprobs), B, T, V, _ptr(tokens),
+                                          _ptr(token_frames), _ptr(token_counts), _ptr(ranks),
+                                          _ptr(count), _ptr(lp_sum), _stream_handle(stream)))
+    if rc != 0:
+        raise FltopError(rc, "fltop_ctc_token_ranks")
+    return ranks, count, lp_sum
 
 
 def stats_dict(stats: torch.Tensor) -> dict:

@@ -18,6 +18,11 @@ int check_threshold(float r) {
     return FLTOP_OK;
 }
 
+int check_options(int32_t top_n, double beam_threshold) {
+    if (top_n < 0 || beam_threshold != beam_threshold) return FLTOP_ERR_BAD_OPTION;
+    return FLTOP_OK;
+}
+
 int check_workspace(const void* ws, size_t bytes, size_t need) {
     if (!ws) return FLTOP_ERR_NULL_POINTER;
     if ((reinterpret_cast<uintptr_t>(ws) & 255u) != 0) return FLTOP_ERR_ALIGNMENT;
@@ -39,18 +44,20 @@ extern "C" size_t fltop_ctc_workspace_bytes(int32_t B, int32_t T, int32_t V, int
 }
 
 extern "C" int fltop_ctc_prune(const float* logprobs, const int32_t* lengths, int32_t B, int32_t T,
-                               int32_t V, int32_t beam, float rel_threshold, void* workspace,
-                               size_t workspace_bytes, void* hip_stream) {
+                               int32_t V, int32_t beam, float rel_threshold, int32_t top_n,
+                               void* workspace, size_t workspace_bytes, void* hip_stream) {
     if (!logprobs || !lengths) return FLTOP_ERR_NULL_POINTER;
     int rc = check_shapes(B, T, V, beam);
     if (rc != FLTOP_OK) return rc;
     rc = check_threshold(rel_threshold);
     if (rc != FLTOP_OK) return rc;
+    rc = check_options(top_n, 0.0);
+    if (rc != FLTOP_OK) return rc;
     rc = check_workspace(workspace, workspace_bytes, fltop_ctc_workspace_bytes(B, T, V, beam));
     if (rc != FLTOP_OK) return rc;
     const fltop::Workspace ws = fltop::carve_workspace(workspace, B, T, V, beam);
-    hipError_t e = fltop::launch_prune(logprobs, lengths, B, T, V, ln_threshold(rel_threshold), ws,
-                                       static_cast<hipStream_t>(hip_stream));
+    hipError_t e = fltop::launch_prune(logprobs, lengths, B, T, V, ln_threshold(rel_threshold),
+                                       top_n, ws, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? FLTOP_OK : FLTOP_ERR_HIP;
 }
 
@@ -106,6 +113,8 @@ extern "C" int fltop_ctc_search(const int32_t* lengths, int32_t B, int32_t T, in
         return FLTOP_ERR_NULL_POINTER;
     int rc = check_shapes(B, T, V, params->beam);
     if (rc != FLTOP_OK) return rc;
+    rc = check_options(0, params->beam_threshold);
+    if (rc != FLTOP_OK) return rc;
     rc = check_nbest(params);
     if (rc != FLTOP_OK) return rc;
     rc = check_workspace(workspace, workspace_bytes,
@@ -126,6 +135,8 @@ extern "C" int fltop_ctc_decode(const float* logprobs, const int32_t* lengths, i
     if (rc != FLTOP_OK) return rc;
     rc = check_threshold(params->rel_threshold);
     if (rc != FLTOP_OK) return rc;
+    rc = check_options(params->top_n, params->beam_threshold);
+    if (rc != FLTOP_OK) return rc;
     rc = check_nbest(params);
     if (rc != FLTOP_OK) return rc;
     rc = check_workspace(workspace, workspace_bytes,
@@ -135,10 +146,25 @@ extern "C" int fltop_ctc_decode(const float* logprobs, const int32_t* lengths, i
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const fltop::Workspace ws = fltop::carve_workspace(workspace, B, T, V, params->beam);
     hipError_t e = fltop::launch_prune(logprobs, lengths, B, T, V,
-                                       ln_threshold(params->rel_threshold), ws, stream);
+                                       ln_threshold(params->rel_threshold), params->top_n, ws,
+                                       stream);
     if (e != hipSuccess) return FLTOP_ERR_HIP;
     return enqueue_search(lengths, B, T, V, params, ws, out_tokens, out_lengths, out_scores, stats,
                           stream);
+}
+
+extern "C" int fltop_ctc_token_ranks(const float* logprobs, int32_t B, int32_t T, int32_t V,
+                                     const int32_t* tokens, const int32_t* token_frames,
+                                     const int32_t* token_counts, int32_t* out_ranks,
+                                     uint64_t* rank_count, double* rank_lp_sum,
+                                     void* hip_stream) {
+    if (!logprobs || !tokens || !token_frames || !token_counts) return FLTOP_ERR_NULL_POINTER;
+    if (B < 1 || T < 1 || V < 2) return FLTOP_ERR_BAD_SHAPE;
+    if (V > FLTOP_MAX_VOCAB) return FLTOP_ERR_VOCAB_TOO_BIG;
+    hipError_t e = fltop::launch_token_ranks(logprobs, B, T, V, tokens, token_frames,
+                                             token_counts, out_ranks, rank_count, rank_lp_sum,
+                                             static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? FLTOP_OK : FLTOP_ERR_HIP;
 }
 
 extern "C" const char* fltop_status_string(int status) {
@@ -152,6 +178,7 @@ extern "C" const char* fltop_status_string(int status) {
         case FLTOP_ERR_VOCAB_TOO_BIG: return "V exceeds FLTOP_MAX_VOCAB";
         case FLTOP_ERR_HIP: return "HIP launch failed";
         case FLTOP_ERR_ALIGNMENT: return "workspace not 256-byte aligned";
+        case FLTOP_ERR_BAD_OPTION: return "top_n negative or beam_threshold NaN";
         default: return "unknown status";
     }
 }

@@ -80,6 +80,9 @@ struct BeamArgs {
     double lm_alpha, lm_beta;
     int32_t B, T, V, beam;
     int32_t lm_in_lds;  // 1: table staged into LDS
+    double beam_window;  // SelectTopK's score window below the frame's best candidate; <= 0: off
+    int32_t* frame_beam;        // optional trace: entries kept after each frame
+    int32_t* out_token_frames;  // optional trace: frame at which each output token was appended
     int32_t* out_tokens;
     int32_t* out_lengths;
     float* out_scores;
@@ -461,6 +464,7 @@ __global__ __launch_bounds__(kThreads) void beam_kernel(BeamArgs a) {
     __shared__ uint64_t bl_D[kExactCap], bl_h[kExactCap];
     __shared__ FrameHdr ring[kChunk];
     __shared__ uint64_t sh_selD, sh_selH, sh_kbest;
+    __shared__ uint64_t sh_minD;  // smallest distance (= best score) among a frame's candidates
     __shared__ int32_t sh_nnew, sh_blcount, sh_best;
     extern __shared__ __align__(16) unsigned char dyn_lds[];
 
@@ -524,6 +528,7 @@ __global__ __launch_bounds__(kThreads) void beam_kernel(BeamArgs a) {
         s0.xanc[0] = 0;
         sh_nnew = 0;
         sh_blcount = 0;
+        sh_minD = kAllOnes;
     }
     TrieNode* trie = a.trie + (int64_t)b * trie_stride;
     const double lm_ub = has_lm ? fmax(0.0, (double)a.lm_bound[0]) : 0.0;
@@ -568,7 +573,10 @@ __global__ __launch_bounds__(kThreads) void beam_kernel(BeamArgs a) {
         const int K = hd.count;
         if (t + 1 < t_end) head_next = FLTOP_RING_HEAD(t + 1);
         if (tid == 0) st_surv += (uint64_t)K;
-        if (n_live == 0) continue;
+        if (n_live == 0) {
+            if (a.frame_beam && tid == 0) a.frame_beam[g] = 0;
+            continue;
+        }
 
         BeamSlab* const cur = &slab[gen];
         BeamSlab* const nxt = &slab[gen ^ 1];
@@ -583,6 +591,7 @@ __global__ __launch_bounds__(kThreads) void beam_kernel(BeamArgs a) {
                 st_cand += (uint64_t)n_live;
                 if ((uint64_t)n_live > st_peak) st_peak = (uint64_t)n_live;
                 st_beam += (uint64_t)n_live;
+                if (a.frame_beam) a.frame_beam[g] = n_live;
             }
             PHASE_MARK(7);
             continue;
@@ -682,6 +691,8 @@ __global__ __launch_bounds__(kThreads) void beam_kernel(BeamArgs a) {
         // ---- selection: find (selD, selH); keep D < selD or (D == selD and hash <= selH)
         uint64_t selD = kAllOnes, selH = kAllOnes;
         uint64_t kbest_key = 0;  // upper bound of the best candidate's key
+        uint64_t Dcut = kAllOnes;  // candidates farther than this from the reference lie
+                                   // outside the score window
         {
             // initial bucket width from the spread of the current beam
             const double est_low = kmin_v + (double)hd.top - 2.0;
@@ -695,6 +706,7 @@ __global__ __launch_bounds__(kThreads) void beam_kernel(BeamArgs a) {
             w.mode = 0;
             w.Dfix = 0;
             int need = beam;
+            const bool windowed = a.beam_window > 0.0;  // uniform
             for (int iter = 0; iter < 40; ++iter) {
                 if (iter > 0) {  // rare: the single histogram is reused for a refined window
                     lds_barrier();
@@ -705,6 +717,8 @@ __global__ __launch_bounds__(kThreads) void beam_kernel(BeamArgs a) {
                 if (D_stay != kAllOnes) hist_add(fc, w, D_stay, tid, -1, hfine, hcoarse);
                 if (cD0 != kAllOnes) hist_add(fc, w, cD0, cI0, cT0, hfine, hcoarse);
                 if (cD1 != kAllOnes) hist_add(fc, w, cD1, cI1, cT1, hfine, hcoarse);
+                uint64_t nearest = D_stay < cD0 ? D_stay : cD0;  // this thread's best candidate
+                nearest = cD1 < nearest ? cD1 : nearest;
                 if (M > kRegCand) {
                     int n_clamp = 0;
                     for (int m = kRegCand; m < M; ++m) {
@@ -713,6 +727,7 @@ __global__ __launch_bounds__(kThreads) void beam_kernel(BeamArgs a) {
                         int se;
                         int32_t tk;
                         const uint64_t D = eval_ext<LM>(fc, e, se, tk);
+                        nearest = D < nearest ? D : nearest;
                         if (D != kAllOnes)
                             hist_add_many(fc, w, D, se, tk, hfine, hcoarse, n_clamp);
                     }
@@ -722,8 +737,20 @@ __global__ __launch_bounds__(kThreads) void beam_kernel(BeamArgs a) {
                         atomicAdd(&hcoarse[kCoarse - 1], (uint32_t)wave_clamp);
                     }
                 }
+                if (windowed && iter == 0 && nearest != kAllOnes)
+                    atomicMin((unsigned long long*)&sh_minD, (unsigned long long)nearest);
                 lds_barrier();
                 PHASE_MARK(2);
+                if (windowed && iter == 0) {
+                    // the frame's best score, exactly; the window's floor in the same fp64
+                    // subtraction a plain implementation does, mapped back to a distance
+                    const uint64_t minD = sh_minD;
+                    if (minD != kAllOnes && minD <= Rk) {
+                        const double floor_score = key_value(Rk - minD) - a.beam_window;
+                        const uint64_t floor_key = order_key(floor_score);
+                        Dcut = floor_key <= Rk ? Rk - floor_key : 0;
+                    }
+                }
                 // every wave scans the histogram redundantly (results are uniform)
                 const int cs = (int)hcoarse[lane];
                 const int incl = wave_inclusive_scan(cs);
@@ -842,6 +869,10 @@ __global__ __launch_bounds__(kThreads) void beam_kernel(BeamArgs a) {
                 }
             }
         }
+        if (Dcut < selD) {  // the score window is narrower than the top-`beam` cut
+            selD = Dcut;
+            selH = kAllOnes;
+        }
         PHASE_MARK(3);
 
         // ---- compaction: selected candidates become the next beam ------------------
@@ -933,6 +964,10 @@ __global__ __launch_bounds__(kThreads) void beam_kernel(BeamArgs a) {
         }
         for (int i = tid; i < kFine; i += kThreads) hfine[i] = 0u;
         if (tid < kCoarse) hcoarse[tid] = 0u;
+        if (tid == 0) {
+            sh_minD = kAllOnes;
+            if (a.frame_beam) a.frame_beam[g] = n_new;
+        }
         if (big)
             for (int k = tid; k < K; k += kThreads) dense_lp[s_tok[k]] = -INFINITY;
         if (n_new > 0) {
@@ -1008,6 +1043,7 @@ __global__ __launch_bounds__(kThreads) void beam_kernel(BeamArgs a) {
         int node = fin.node[best];
         int depth = fin.plen[best];
         int32_t* dst = a.out_tokens + (int64_t)b * a.T;
+        int32_t* born = a.out_token_frames ? a.out_token_frames + (int64_t)b * a.T : nullptr;
         while (depth > 0) {  // uniform: node/depth are re-read from LDS after each batch
             if (tid == 0) {
                 int n = 0;
@@ -1034,6 +1070,7 @@ __global__ __launch_bounds__(kThreads) void beam_kernel(BeamArgs a) {
                 while (dp > stop && nd > 0 && (int64_t)nd < a.trie_stride) {
                     const TrieNode tn = trie[nd];
                     dst[dp - 1] = tn.tok;
+                    if (born) born[dp - 1] = (nd - 1) / beam;  // node id = 1 + frame * beam + slot
                     nd = tn.parent;
                     --dp;
                 }
@@ -1088,6 +1125,9 @@ hipError_t launch_beam(const int32_t* lengths, int32_t B, int32_t T, int32_t V,
     a.lm_bound = ws.lm_bound;
     a.lm_alpha = (double)p.lm_weight;
     a.lm_beta = (double)p.insertion_bonus;
+    a.beam_window = p.beam_threshold;
+    a.frame_beam = p.frame_beam;
+    a.out_token_frames = p.out_token_frames;
     a.B = B;
     a.T = T;
     a.V = V;

@@ -82,7 +82,12 @@ inline Workspace carve_workspace(void* base, int32_t B, int32_t T, int32_t V, in
 
 // Launchers (defined next to their kernels); each returns a hipError_t.
 hipError_t launch_prune(const float* logprobs, const int32_t* lengths, int32_t B, int32_t T,
-                        int32_t V, float ln_r, const Workspace& ws, hipStream_t stream);
+                        int32_t V, float ln_r, int32_t top_n, const Workspace& ws,
+                        hipStream_t stream);
+hipError_t launch_token_ranks(const float* logprobs, int32_t B, int32_t T, int32_t V,
+                              const int32_t* tokens, const int32_t* token_frames,
+                              const int32_t* token_counts, int32_t* out_ranks,
+                              uint64_t* rank_count, double* rank_lp_sum, hipStream_t stream);
 hipError_t launch_unpack(const Workspace& ws, const int32_t* lengths, int32_t B, int32_t T,
                          int32_t V, int32_t* counts, int32_t* tokens, float* values,
                          float* frame_max, hipStream_t stream);

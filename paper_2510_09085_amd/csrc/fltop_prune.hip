@@ -4,6 +4,13 @@
 // batch at once, ahead of the beam search, and is bound by the HBM read of the
 // emissions.
 //
+// The optional static stage of Algorithm 1 (only the N best tokens of a frame take the
+// threshold test at all) is applied to the threshold's survivors: both tests keep an
+// upper part of the frame's descending order, so "N best, then threshold" equals
+// "threshold, then the N best of what is left".  The N-th best survivor is found with a
+// bitwise search over an order-preserving integer image of the fp32 values (32 counting
+// steps inside the frame's lane group); equal values are taken in ascending token order.
+//
 // Output per frame: a 64-byte header (count, top emission, survivors 0..5 in
 // ascending token order) and, for frames with more than six survivors, survivors
 // 6.. as (token, log-prob) records at a fixed place (slot = rank).
@@ -78,6 +85,26 @@ __device__ __forceinline__ int group_inclusive_scan(int c, int lg) {
     return v;
 }
 
+// Sum over the LPF lanes of a frame's lane group, result in every lane (same exchange
+// pattern as group_max).
+template <int LPF>
+__device__ __forceinline__ int group_sum(int x) {
+    if (LPF >= 2) x += dpp_int<0xB1, 0xf>(0, x);
+    if (LPF >= 4) x += dpp_int<0x4E, 0xf>(0, x);
+    if (LPF >= 8) x += dpp_int<0x141, 0xf>(0, x);
+    if (LPF >= 16) x += dpp_int<0x140, 0xf>(0, x);
+    if (LPF >= 32) x += __shfl_xor(x, 16, kWave);
+    if (LPF >= 64) x += __shfl_xor(x, 32, kWave);
+    return x;
+}
+
+// Order-preserving image of an fp32 value (larger value, larger integer); -0.0 counts
+// as +0.0, as it does for a floating-point comparison.
+__device__ __forceinline__ uint32_t order_bits(float x) {
+    const uint32_t b = (uint32_t)__float_as_int(x + 0.0f);
+    return (b >> 31) ? ~b : (b | 0x80000000u);
+}
+
 template <int LPF, int ITERS, bool VEC4>
 struct FrameRegs {
     float x[ITERS][4];
@@ -111,7 +138,8 @@ __device__ __forceinline__ void load_frame(FrameRegs<LPF, ITERS, VEC4>& r,
 template <int LPF, int ITERS, bool VEC4>
 __global__ __launch_bounds__(kThreads) void prune_kernel(
     const float* __restrict__ logprobs, const int32_t* __restrict__ lengths, int32_t B, int32_t T,
-    int32_t V, float ln_r, FrameHdr* __restrict__ hdr, Survivor* __restrict__ rec) {
+    int32_t V, float ln_r, int32_t top_n, FrameHdr* __restrict__ hdr,
+    Survivor* __restrict__ rec) {
     constexpr int FPR = kWave / LPF;  // frames per wave round
     static_assert(LPF == kWave || ITERS == 1, "several chunks per lane only for whole-wave frames");
     static_assert(ITERS <= 8 || ITERS == 16, "flag word holds 4*ITERS <= 64 bits");
@@ -169,14 +197,75 @@ __global__ __launch_bounds__(kThreads) void prune_kernel(
         // memory system a read-modify-write.
         Survivor* list = rec + g * V;
         FrameHdr* img = &stage[threadIdx.x / kWave][gw];
+        unsigned keep[ITERS];  // bit e of keep[it]: value x[it][e] survives
+        int kept_here = 0;
+#pragma unroll
+        for (int it = 0; it < ITERS; ++it) {
+            const int v0 = 4 * (lg + LPF * it);
+            keep[it] = 0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                keep[it] |= (fr.valid && (v0 + e < V) && (fr.x[it][e] >= thr)) ? (1u << e) : 0u;
+            kept_here += __popc(keep[it]);
+        }
+        // ---- static stage: at most top_n survivors, the best by (value desc, token asc) ----
+        if (top_n > 0) {  // uniform
+            const int kept_frame = group_sum<LPF>(kept_here);
+            if (__any(kept_frame > top_n)) {  // wave-uniform: every lane joins the exchanges
+                // largest `cut` with at least top_n kept values >= cut: the top_n-th best value
+                uint32_t cut = 0;
+                for (int bit = 31; bit >= 0; --bit) {
+                    const uint32_t trial = cut | (1u << bit);
+                    int c = 0;
+#pragma unroll
+                    for (int it = 0; it < ITERS; ++it)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            c += (((keep[it] >> e) & 1u) && order_bits(fr.x[it][e]) >= trial) ? 1 : 0;
+                    if (group_sum<LPF>(c) >= top_n) cut = trial;
+                }
+                // everything above the cut stays; of the values equal to it, the first few
+                // in token order fill the remaining places
+                int above = 0;
+#pragma unroll
+                for (int it = 0; it < ITERS; ++it)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        above += (((keep[it] >> e) & 1u) && order_bits(fr.x[it][e]) > cut) ? 1 : 0;
+                const int places = top_n - group_sum<LPF>(above);
+                int equal_before = 0;  // values equal to the cut at lower token ids
+#pragma unroll
+                for (int it = 0; it < ITERS; ++it) {
+                    unsigned eq = 0;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        eq |= (((keep[it] >> e) & 1u) && order_bits(fr.x[it][e]) == cut) ? (1u << e)
+                                                                                         : 0u;
+                    const int n_eq = __popc(eq);
+                    const int incl = group_inclusive_scan<LPF>(n_eq, lg);
+                    int r = equal_before + incl - n_eq;
+                    unsigned stay = 0;  // above the cut, or equal to it and early enough
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        if ((eq >> e) & 1u) {
+                            if (r < places) stay |= 1u << e;
+                            ++r;
+                        } else if (order_bits(fr.x[it][e]) > cut) {
+                            stay |= 1u << e;
+                        }
+                    }
+                    if (kept_frame > top_n) keep[it] &= stay;
+                    if (LPF == kWave)
+                        equal_before += __builtin_amdgcn_readlane(incl, kWave - 1);
+                    // LPF < 64 has ITERS == 1: no further chunk
+                }
+            }
+        }
         int total = 0;
 #pragma unroll
         for (int it = 0; it < ITERS; ++it) {
             const int v0 = 4 * (lg + LPF * it);
-            unsigned bits = 0;
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-                bits |= (fr.valid && (v0 + e < V) && (fr.x[it][e] >= thr)) ? (1u << e) : 0u;
+            unsigned bits = keep[it];
             const int cnt = __popc(bits);
             const int incl = group_inclusive_scan<LPF>(cnt, lg);
             int rank = total + incl - cnt;
@@ -281,7 +370,8 @@ __global__ __launch_bounds__(kThreads) void lm_bound_kernel(const float* __restr
 
 template <int LPF, int ITERS>
 hipError_t launch_prune_t(const float* logprobs, const int32_t* lengths, int32_t B, int32_t T,
-                          int32_t V, float ln_r, const Workspace& ws, hipStream_t stream) {
+                          int32_t V, float ln_r, int32_t top_n, const Workspace& ws,
+                          hipStream_t stream) {
     constexpr int FPR = kWave / LPF;
     constexpr int U = ITERS >= 4 ? 1 : (ITERS == 2 ? 2 : 4);
     // grid = (blocks per utterance, B): about 2048 workgroups in all (8 per CU), but never
@@ -295,21 +385,23 @@ hipError_t launch_prune_t(const float* logprobs, const int32_t* lengths, int32_t
     const bool vec4 = (V % 4 == 0) && ((reinterpret_cast<uintptr_t>(logprobs) & 15u) == 0);
     if (vec4)
         hipLaunchKernelGGL((prune_kernel<LPF, ITERS, true>), grid, dim3(kThreads), 0, stream,
-                           logprobs, lengths, B, T, V, ln_r, ws.hdr, ws.rec);
+                           logprobs, lengths, B, T, V, ln_r, top_n, ws.hdr, ws.rec);
     else
         hipLaunchKernelGGL((prune_kernel<LPF, ITERS, false>), grid, dim3(kThreads), 0, stream,
-                           logprobs, lengths, B, T, V, ln_r, ws.hdr, ws.rec);
+                           logprobs, lengths, B, T, V, ln_r, top_n, ws.hdr, ws.rec);
     return hipGetLastError();
 }
 
 }  // namespace
 
 hipError_t launch_prune(const float* logprobs, const int32_t* lengths, int32_t B, int32_t T,
-                        int32_t V, float ln_r, const Workspace& ws, hipStream_t stream) {
+                        int32_t V, float ln_r, int32_t top_n, const Workspace& ws,
+                        hipStream_t stream) {
+    if (top_n >= V) top_n = 0;  // the static stage keeps everything
     const int lpf = lanes_per_frame(V);
     const int chunks = (V + 4 * lpf - 1) / (4 * lpf);  // 16-byte chunks per lane
 #define FLTOP_PRUNE_CASE(L, I) \
-    return launch_prune_t<L, I>(logprobs, lengths, B, T, V, ln_r, ws, stream)
+    return launch_prune_t<L, I>(logprobs, lengths, B, T, V, ln_r, top_n, ws, stream)
     switch (lpf) {
         case 1: FLTOP_PRUNE_CASE(1, 1);
         case 2: FLTOP_PRUNE_CASE(2, 1);

@@ -39,16 +39,16 @@ def test_header_constants_match_binding():
     assert int(re.search(r"#define FLTOP_MAX_VOCAB\s+(\d+)", text).group(1)) == binding.MAX_VOCAB
     codes = dict(re.findall(r"#define (FLTOP_(?:OK|ERR_[A-Z_]+))\s+(-?\d+)", text))
     assert codes["FLTOP_OK"] == "0"
-    assert sorted(int(v) for v in codes.values()) == list(range(-8, 1))
+    assert sorted(int(v) for v in codes.values()) == list(range(-9, 1))
 
 
 def test_status_strings(lib):
     seen = set()
-    for code in range(-8, 1):
+    for code in range(-9, 1):
         s = binding.status_string(code)
         assert s and s != "unknown status"
         seen.add(s)
-    assert len(seen) == 9
+    assert len(seen) == 10
     assert binding.status_string(-99) == "unknown status"
 
 
@@ -109,9 +109,20 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     q.nbest_count = 4096  # some but not all n-best pointers
     assert call(params=q) == -1
     # the stand-alone prune stage validates the same way
-    assert lib.fltop_ctc_prune(None, fake, 2, 10, 32, 8, 0.01, fake, need, None) == -1
-    assert lib.fltop_ctc_prune(fake, fake, 2, 10, 32, 8, 2.0, fake, need, None) == -4
-    assert lib.fltop_ctc_prune(fake, fake, 2, 10, 32, 8, 0.01, fake, 16, None) == -5
+    assert lib.fltop_ctc_prune(None, fake, 2, 10, 32, 8, 0.01, 0, fake, need, None) == -1
+    assert lib.fltop_ctc_prune(fake, fake, 2, 10, 32, 8, 2.0, 0, fake, need, None) == -4
+    assert lib.fltop_ctc_prune(fake, fake, 2, 10, 32, 8, 0.01, 0, fake, 16, None) == -5
+    assert lib.fltop_ctc_prune(fake, fake, 2, 10, 32, 8, 0.01, -1, fake, need, None) == -9
+    for field, bad in (("top_n", -2), ("beam_threshold", float("nan"))):
+        q = binding.FltopParams()
+        q.beam = 8
+        q.rel_threshold = 0.5
+        setattr(q, field, bad)
+        assert call(params=q) == -9
+    assert lib.fltop_ctc_token_ranks(None, 2, 10, 32, fake, fake, fake, None, None, None,
+                                     None) == -1
+    assert lib.fltop_ctc_token_ranks(fake, 2, 10, 1, fake, fake, fake, None, None, None,
+                                     None) == -2
     assert lib.fltop_ctc_unpack_survivors(fake, need, fake, 2, 10, 32, 8, None, fake, fake, None,
                                           None) == -1
     assert lib.fltop_ctc_unpack_survivors(fake, need, None, 2, 10, 32, 8, fake, fake, fake, None,

@@ -61,10 +61,12 @@ class Job:
         self.sc = torch.zeros(w.B, dtype=torch.float32, device=dev)
         self.stats = torch.zeros(len(binding.STATS_FIELDS), dtype=torch.int64, device=dev)
 
-    def params(self, r):
+    def params(self, r, top_n=0, beam_threshold=0.0):
         p = self.binding.FltopParams()
         p.beam = self.w.beam
         p.rel_threshold = float(r)
+        p.top_n = int(top_n)
+        p.beam_threshold = float(beam_threshold)
         if self.lm is not None:
             p.lm_table = self.lm.data_ptr()
             p.lm_weight = self.w.lm_weight
@@ -77,9 +79,9 @@ class Job:
         if rc != 0:
             raise self.binding.FltopError(rc, "fltop_ctc_decode")
 
-    def prune(self, r, copy=0):
+    def prune(self, r, copy=0, top_n=0):
         rc = self.binding.prune_raw(self.lp[copy], self.ln, self.w.beam, r, self.ws,
-                                    self.ws.numel())
+                                    self.ws.numel(), top_n=top_n)
         if rc != 0:
             raise self.binding.FltopError(rc, "fltop_ctc_prune")
 
@@ -159,6 +161,59 @@ def emission_read_roofline(torch, binding, synth, w, r, dev, target_bytes=1 << 3
             "isolated_launch_us": round(sum(single) / len(single) * 1e3, 2),
             "algorithmic_bytes": nbytes, "written_bytes_approx": prune_written_bytes(st),
             "rotated_copies": copies, "launches": n}
+
+
+def paper_arms(torch, binding, job, window):
+    """The three arms of the paper's Sec. 4 on this workload's synthetic emissions: all
+    tokens (its Baseline), static Top-4, and FLToP (N = 4, R = 0.007), each with the score
+    window of SelectTopK at `window`; per arm the decode time, the hypotheses kept per time
+    step (Sec. 4.4) and, for the all-token arm, how often the decoded tokens sat at each
+    position of their frame's descending emission order (Sec. 4.1)."""
+    w = job.w
+    dev = job.ln.device
+    frame_beam = torch.full((w.B, w.T), -1, dtype=torch.int32, device=dev)
+    token_frames = torch.full((w.B, w.T), -1, dtype=torch.int32, device=dev)
+    arms = []
+    for name, n, r in (("all_tokens", 0, 0.0), ("top4", 4, 0.0), ("fltop_n4_r0.007", 4, 0.007)):
+        p = job.params(r, top_n=n, beam_threshold=window)
+        ms = event_times_ms(torch, lambda i: job.decode(p), 10)
+        avg = sum(ms) / len(ms)
+        prune_ms = event_times_ms(torch, lambda i: job.prune(r, top_n=n), 10)
+        search_ms = event_times_ms(torch, lambda i: job.search(p), 10)
+        frame_beam.fill_(-1)
+        token_frames.fill_(-1)
+        p.frame_beam = frame_beam.data_ptr()
+        p.out_token_frames = token_frames.data_ptr()
+        st = job.stats_of(p)
+        fb = frame_beam.cpu().numpy()
+        live = fb[fb >= 0]
+        q = [float(x) for x in __import__("numpy").percentile(live, [25, 50, 75])]
+        arm = {"arm": name, "top_n": n, "rel_threshold": r, "beam_threshold": window,
+               "ms": round(avg, 4), "frames_per_s": round(job.frames / (avg * 1e-3), 1),
+               "stage_us": {"prune": round(sum(prune_ms) / len(prune_ms) * 1e3, 2),
+                            "search": round(sum(search_ms) / len(search_ms) * 1e3, 2)},
+               "mean_survivors": round(st["sum_survivors"] / st["frames"], 3),
+               "mean_candidates": round(st["sum_candidates"] / st["frames"], 2),
+               "hypotheses_per_step": {"mean": round(float(live.mean()), 2), "p25": q[0],
+                                       "median": q[1], "p75": q[2], "max": int(live.max())}}
+        if n == 0:
+            _, count, lp_sum = binding.token_ranks(job.lp[0], job.tok, token_frames, job.olen)
+            torch.cuda.synchronize()
+            count, lp_sum = count.cpu().numpy(), lp_sum.cpu().numpy()
+            total = max(1, int(count.sum()))
+            arm["chosen_token_position"] = {
+                "tokens": int(count.sum()),
+                "share_by_position": [round(float(c) / total, 6) for c in count[:8]],
+                "share_within_top4": round(float(count[:4].sum()) / total, 6),
+                "mean_logprob_by_position": [round(float(s_ / c), 4) if c else None
+                                             for s_, c in zip(lp_sum[:8], count[:8])]}
+        arms.append(arm)
+    base = arms[0]
+    for arm in arms[1:]:
+        arm["speedup_vs_all_tokens"] = round(base["ms"] / arm["ms"], 2)
+        arm["hypotheses_ratio_vs_all_tokens"] = round(
+            base["hypotheses_per_step"]["mean"] / arm["hypotheses_per_step"]["mean"], 2)
+    return arms
 
 
 def cpu_baseline(synth, w, r, frames_budget_s=12.0):
@@ -352,6 +407,10 @@ def main():
                 "survivor_record_bytes_ratio": round(
                     base["survivor_record_bytes"] / mine["survivor_record_bytes"], 2),
             }
+        # ---- the paper's three arms, with its score window (beam-threshold 25) and a
+        #      tighter one that actually bites at this beam size
+        result["paper_arms"] = {"window_25": paper_arms(torch, binding, job, 25.0),
+                                "window_6": paper_arms(torch, binding, job, 6.0)}
         result["paper_context"] = ("paper reports 10.5x runtime speedup and 2.78x fewer beams "
                                    "(FLToP N=4,R=0.007 vs all-32-token baseline) for a CPU "
                                    "flashlight/KenLM decoder on LibriSpeech, wav2vec2-large "

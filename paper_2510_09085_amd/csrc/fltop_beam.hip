@@ -172,6 +172,27 @@ __device__ __forceinline__ int wave_inclusive_scan(int v0) {
     return v1;
 }
 
+// Minimum of an unsigned value over the wavefront, returned in every lane: pairwise
+// exchanges inside a row of 16 lanes, then lane 15 / lane 31 carried into the next rows
+// (the last lane then holds the result).
+__device__ __forceinline__ uint32_t wave_min_u32(uint32_t v) {
+    v = min(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0xB1, 0xf, 0xf, false));
+    v = min(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x4E, 0xf, 0xf, false));
+    v = min(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x141, 0xf, 0xf, false));
+    v = min(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x140, 0xf, 0xf, false));
+    v = min(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x142, 0xa, 0xf, false));
+    v = min(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x143, 0xc, 0xf, false));
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, kWave - 1);
+}
+
+// The same for a 64-bit value: high words first, then the low words of the lanes that
+// hold the smallest high word.
+__device__ __forceinline__ uint64_t wave_min_u64(uint64_t v) {
+    const uint32_t hi = wave_min_u32((uint32_t)(v >> 32));
+    const uint32_t lo = wave_min_u32((uint32_t)(v >> 32) == hi ? (uint32_t)v : 0xFFFFFFFFu);
+    return ((uint64_t)hi << 32) | lo;
+}
+
 // dynamic LDS: dense_lp[V] fp32, s_tok[V] u16, then (optionally) the LM table
 __host__ __device__ inline size_t lm_lds_offset(int V) {
     return (((size_t)V * (sizeof(float) + sizeof(uint16_t))) + 15) / 16 * 16;
@@ -737,8 +758,12 @@ __global__ __launch_bounds__(kThreads) void beam_kernel(BeamArgs a) {
                         atomicAdd(&hcoarse[kCoarse - 1], (uint32_t)wave_clamp);
                     }
                 }
-                if (windowed && iter == 0 && nearest != kAllOnes)
-                    atomicMin((unsigned long long*)&sh_minD, (unsigned long long)nearest);
+                if (windowed && iter == 0) {  // one LDS atomic per wavefront
+                    const uint64_t wave_nearest = wave_min_u64(nearest);
+                    if (lane == 0 && wave_nearest != kAllOnes)
+                        atomicMin((unsigned long long*)&sh_minD,
+                                  (unsigned long long)wave_nearest);
+                }
                 lds_barrier();
                 PHASE_MARK(2);
                 if (windowed && iter == 0) {

@@ -165,6 +165,34 @@ int fltop_ctc_unpack_survivors(const void* workspace, size_t workspace_bytes,
                                int32_t beam, int32_t* counts, int32_t* tokens, float* values,
                                float* frame_max, void* hip_stream);
 
+/* Streaming (chunked) decoding: the emissions of an utterance arrive in pieces and the beam
+ * is carried from call to call, so that partial transcripts are available while audio is
+ * still coming in (the real-time use the paper's Sec. 1 aims at).  Decoding T_total frames
+ * in chunks gives exactly what fltop_ctc_decode gives on the whole utterance.
+ *
+ *   state    dev, 256-byte aligned, >= fltop_ctc_stream_state_bytes(B, T_total, beam): per
+ *            utterance the carried beam, then the prefix trie for up to T_total frames.
+ *            Caller-owned; one state per batch of streams; the same B and beam in every call.
+ *   fltop_ctc_stream_begin   resets every stream of the batch to the empty prefix.
+ *   fltop_ctc_stream_decode  consumes the next chunk: logprobs dev [B,T_chunk,V], lengths
+ *            dev [B] = valid frames of this chunk per stream (0 for a stream that has
+ *            ended; frames beyond T_total in all are ignored); workspace sized by
+ *            fltop_ctc_workspace_bytes(B, T_chunk, V, beam).  Outputs as for
+ *            fltop_ctc_decode but for everything decoded so far: out_tokens dev
+ *            [B,T_total]; the traces and the n-best token rows of params, if given, are
+ *            [B,T_total] / [B,beam,T_total] and indexed by the frame number since the
+ *            stream began.  stats count this chunk only.
+ * Calls on one state must be ordered (same stream, or synchronised by the caller). */
+size_t fltop_ctc_stream_state_bytes(int32_t B, int32_t T_total, int32_t beam);
+int fltop_ctc_stream_begin(void* state, size_t state_bytes, int32_t B, int32_t T_total,
+                           int32_t beam, void* hip_stream);
+int fltop_ctc_stream_decode(const float* logprobs, const int32_t* lengths,
+                            int32_t B, int32_t T_chunk, int32_t V, const fltop_params* params,
+                            void* workspace, size_t workspace_bytes,
+                            void* state, size_t state_bytes, int32_t T_total,
+                            int32_t* out_tokens, int32_t* out_lengths, float* out_scores,
+                            fltop_stats* stats, void* hip_stream);
+
 /* "Index of the chosen token" statistic (paper Sec. 4.1): for every token i of the
  * returned prefixes, its position in the descending sort of the emissions of the frame
  * out_token_frames[b][i] (0 = top emission; equal emissions in ascending token order).

@@ -19,7 +19,8 @@ MAX_BEAM = 128
 MAX_VOCAB = 4096
 
 EXPORTS = ("fltop_ctc_workspace_bytes", "fltop_ctc_decode", "fltop_ctc_prune", "fltop_ctc_search",
-           "fltop_ctc_unpack_survivors", "fltop_ctc_token_ranks", "fltop_status_string")
+           "fltop_ctc_unpack_survivors", "fltop_ctc_token_ranks", "fltop_ctc_stream_state_bytes",
+           "fltop_ctc_stream_begin", "fltop_ctc_stream_decode", "fltop_status_string")
 
 
 class FltopParams(ctypes.Structure):
@@ -79,6 +80,13 @@ def load():
     lib.fltop_ctc_token_ranks.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]
     lib.fltop_ctc_unpack_survivors.restype = ctypes.c_int
     lib.fltop_ctc_unpack_survivors.argtypes = [vp, sz, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp]
+    lib.fltop_ctc_stream_state_bytes.restype = sz
+    lib.fltop_ctc_stream_state_bytes.argtypes = [i32, i32, i32]
+    lib.fltop_ctc_stream_begin.restype = ctypes.c_int
+    lib.fltop_ctc_stream_begin.argtypes = [vp, sz, i32, i32, i32, vp]
+    lib.fltop_ctc_stream_decode.restype = ctypes.c_int
+    lib.fltop_ctc_stream_decode.argtypes = [vp, vp, i32, i32, i32, ctypes.POINTER(FltopParams),
+                                            vp, sz, vp, sz, i32, vp, vp, vp, vp, vp]
     lib.fltop_status_string.restype = ctypes.c_char_p
     lib.fltop_status_string.argtypes = [ctypes.c_int]
     _lib = lib
@@ -257,6 +265,67 @@ def token_ranks(logprobs: torch.Tensor, tokens: torch.Tensor, token_frames: torc
     if rc != 0:
         raise FltopError(rc, "fltop_ctc_token_ranks")
     return ranks, count, lp_sum
+
+
+class Stream:
+    """Chunked decoding of a batch of B streams of up to T_total frames each: owns the
+    carried state, the output tensors and a workspace for chunks of up to T_chunk frames.
+    feed() enqueues one chunk; the outputs then describe everything decoded so far."""
+
+    def __init__(self, B: int, T_total: int, T_chunk: int, V: int, beam: int,
+                 rel_threshold: float, device, *, top_n: int = 0, beam_threshold: float = 0.0,
+                 lm_table: Optional[torch.Tensor] = None, lm_weight: float = 0.0,
+                 insertion_bonus: float = 0.0, want_traces: bool = False):
+        lib = load()
+        self.B, self.T_total, self.T_chunk, self.V = B, T_total, T_chunk, V
+        nbytes = int(lib.fltop_ctc_stream_state_bytes(B, T_total, beam))
+        if nbytes == 0:
+            raise FltopError(-2, "fltop_ctc_stream_state_bytes")
+        self.state = torch.empty(nbytes, dtype=torch.uint8, device=device)
+        self.workspace = alloc_workspace(B, T_chunk, V, beam, device)
+        self.tokens = torch.full((B, T_total), -1, dtype=torch.int32, device=device)
+        self.lengths = torch.zeros(B, dtype=torch.int32, device=device)
+        self.scores = torch.zeros(B, dtype=torch.float32, device=device)
+        self.stats = torch.zeros(len(STATS_FIELDS), dtype=torch.int64, device=device)
+        p = FltopParams()
+        p.beam = int(beam)
+        p.rel_threshold = float(rel_threshold)
+        p.top_n = int(top_n)
+        p.beam_threshold = float(beam_threshold)
+        p.lm_weight = float(lm_weight)
+        p.insertion_bonus = float(insertion_bonus)
+        self._lm = lm_table
+        if lm_table is not None:
+            p.lm_table = lm_table.data_ptr()
+        self.frame_beam = self.token_frames = None
+        if want_traces:
+            self.frame_beam = torch.full((B, T_total), -1, dtype=torch.int32, device=device)
+            self.token_frames = torch.full((B, T_total), -1, dtype=torch.int32, device=device)
+            p.frame_beam = self.frame_beam.data_ptr()
+            p.out_token_frames = self.token_frames.data_ptr()
+        self.params = p
+        self.begin()
+
+    def begin(self, stream=None):
+        rc = int(load().fltop_ctc_stream_begin(_ptr(self.state), self.state.numel(), self.B,
+                                               self.T_total, self.params.beam,
+                                               _stream_handle(stream)))
+        if rc != 0:
+            raise FltopError(rc, "fltop_ctc_stream_begin")
+
+    def feed(self, logprobs: torch.Tensor, lengths: torch.Tensor, stream=None):
+        """logprobs [B,Tc,V] (Tc <= T_chunk), lengths [B]: valid frames of this chunk."""
+        _check_inputs(logprobs, lengths)
+        B, Tc, V = logprobs.shape
+        if B != self.B or V != self.V or Tc > self.T_chunk:
+            raise ValueError("chunk shape does not fit this stream")
+        rc = int(load().fltop_ctc_stream_decode(
+            _ptr(logprobs), _ptr(lengths), B, Tc, V, ctypes.byref(self.params),
+            _ptr(self.workspace), self.workspace.numel(), _ptr(self.state), self.state.numel(),
+            self.T_total, _ptr(self.tokens), _ptr(self.lengths), _ptr(self.scores),
+            _ptr(self.stats), _stream_handle(stream)))
+        if rc != 0:
+            raise FltopError(rc, "fltop_ctc_stream_decode")
 
 
 def stats_dict(stats: torch.Tensor) -> dict:

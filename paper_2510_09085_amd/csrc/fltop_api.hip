@@ -89,17 +89,17 @@ int check_nbest(const fltop_params* p) {
 }
 
 int enqueue_search(const int32_t* lengths, int32_t B, int32_t T, int32_t V,
-                   const fltop_params* params, const fltop::Workspace& ws, int32_t* out_tokens,
-                   int32_t* out_lengths, float* out_scores, fltop_stats* stats,
-                   hipStream_t stream) {
+                   const fltop_params* params, const fltop::Workspace& ws,
+                   const fltop::StreamSpace* carried, int32_t* out_tokens, int32_t* out_lengths,
+                   float* out_scores, fltop_stats* stats, hipStream_t stream) {
     hipError_t e = hipSuccess;
     if (params->lm_table) {
         e = fltop::launch_lm_bound(params->lm_table, V, params->lm_weight, params->insertion_bonus,
                                    ws.lm_bound, stream);
         if (e != hipSuccess) return FLTOP_ERR_HIP;
     }
-    e = fltop::launch_beam(lengths, B, T, V, *params, ws, out_tokens, out_lengths, out_scores,
-                           stats, stream);
+    e = fltop::launch_beam(lengths, B, T, V, *params, ws, carried, out_tokens, out_lengths,
+                           out_scores, stats, stream);
     return e == hipSuccess ? FLTOP_OK : FLTOP_ERR_HIP;
 }
 
@@ -121,8 +121,8 @@ extern "C" int fltop_ctc_search(const int32_t* lengths, int32_t B, int32_t T, in
                          fltop_ctc_workspace_bytes(B, T, V, params->beam));
     if (rc != FLTOP_OK) return rc;
     const fltop::Workspace ws = fltop::carve_workspace(workspace, B, T, V, params->beam);
-    return enqueue_search(lengths, B, T, V, params, ws, out_tokens, out_lengths, out_scores, stats,
-                          static_cast<hipStream_t>(hip_stream));
+    return enqueue_search(lengths, B, T, V, params, ws, nullptr, out_tokens, out_lengths,
+                          out_scores, stats, static_cast<hipStream_t>(hip_stream));
 }
 
 extern "C" int fltop_ctc_decode(const float* logprobs, const int32_t* lengths, int32_t B, int32_t T,
@@ -149,8 +149,59 @@ extern "C" int fltop_ctc_decode(const float* logprobs, const int32_t* lengths, i
                                        ln_threshold(params->rel_threshold), params->top_n, ws,
                                        stream);
     if (e != hipSuccess) return FLTOP_ERR_HIP;
-    return enqueue_search(lengths, B, T, V, params, ws, out_tokens, out_lengths, out_scores, stats,
-                          stream);
+    return enqueue_search(lengths, B, T, V, params, ws, nullptr, out_tokens, out_lengths,
+                          out_scores, stats, stream);
+}
+
+extern "C" size_t fltop_ctc_stream_state_bytes(int32_t B, int32_t T_total, int32_t beam) {
+    if (check_shapes(B, T_total, 2, beam) != FLTOP_OK) return 0;
+    return fltop::carve_stream(nullptr, B, T_total, beam).bytes;
+}
+
+extern "C" int fltop_ctc_stream_begin(void* state, size_t state_bytes, int32_t B, int32_t T_total,
+                                      int32_t beam, void* hip_stream) {
+    int rc = check_shapes(B, T_total, 2, beam);
+    if (rc != FLTOP_OK) return rc;
+    rc = check_workspace(state, state_bytes, fltop_ctc_stream_state_bytes(B, T_total, beam));
+    if (rc != FLTOP_OK) return rc;
+    const fltop::StreamSpace sp = fltop::carve_stream(state, B, T_total, beam);
+    hipError_t e = fltop::launch_stream_begin(sp.records, B, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? FLTOP_OK : FLTOP_ERR_HIP;
+}
+
+extern "C" int fltop_ctc_stream_decode(const float* logprobs, const int32_t* lengths, int32_t B,
+                                       int32_t T_chunk, int32_t V, const fltop_params* params,
+                                       void* workspace, size_t workspace_bytes, void* state,
+                                       size_t state_bytes, int32_t T_total, int32_t* out_tokens,
+                                       int32_t* out_lengths, float* out_scores,
+                                       fltop_stats* stats, void* hip_stream) {
+    if (!logprobs || !lengths || !params || !out_tokens || !out_lengths || !out_scores)
+        return FLTOP_ERR_NULL_POINTER;
+    int rc = check_shapes(B, T_chunk, V, params->beam);
+    if (rc != FLTOP_OK) return rc;
+    if (T_total < T_chunk) return FLTOP_ERR_BAD_SHAPE;
+    rc = check_threshold(params->rel_threshold);
+    if (rc != FLTOP_OK) return rc;
+    rc = check_options(params->top_n, params->beam_threshold);
+    if (rc != FLTOP_OK) return rc;
+    rc = check_nbest(params);
+    if (rc != FLTOP_OK) return rc;
+    rc = check_workspace(workspace, workspace_bytes,
+                         fltop_ctc_workspace_bytes(B, T_chunk, V, params->beam));
+    if (rc != FLTOP_OK) return rc;
+    rc = check_workspace(state, state_bytes,
+                         fltop_ctc_stream_state_bytes(B, T_total, params->beam));
+    if (rc != FLTOP_OK) return rc;
+
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const fltop::Workspace ws = fltop::carve_workspace(workspace, B, T_chunk, V, params->beam);
+    const fltop::StreamSpace sp = fltop::carve_stream(state, B, T_total, params->beam);
+    hipError_t e = fltop::launch_prune(logprobs, lengths, B, T_chunk, V,
+                                       ln_threshold(params->rel_threshold), params->top_n, ws,
+                                       stream);
+    if (e != hipSuccess) return FLTOP_ERR_HIP;
+    return enqueue_search(lengths, B, T_chunk, V, params, ws, &sp, out_tokens, out_lengths,
+                          out_scores, stats, stream);
 }
 
 extern "C" int fltop_ctc_token_ranks(const float* logprobs, int32_t B, int32_t T, int32_t V,

@@ -69,6 +69,25 @@ struct Links {
     int32_t ht[kHashSlots];      // open addressing: slot -> beam index, keyed by prefix hash
 };
 
+// What a streaming (chunked) decode carries from one call to the next, per utterance: the
+// beam and its links as they stand after the last frame seen, plus the scalars the frame
+// loop keeps in registers.  The prefix trie lives behind the array of these records.
+struct StreamState {
+    int32_t frames_done;  // frames decoded so far (= trie frame index of the next one)
+    int32_t n_live;
+    int32_t collapsed;
+    int32_t pad;
+    double bias, kmax, kmin;
+    BeamSlab slab;
+    int32_t par[kMaxBeam];
+    int32_t first_kid[kMaxBeam];
+    int32_t next_kid[kMaxBeam];
+    uint32_t kidmask[kMaxBeam];
+};
+static_assert(sizeof(StreamState) % 8 == 0, "records sit in an array: doubles stay aligned");
+static_assert(offsetof(Links, ht) == 4 * kMaxBeam * sizeof(int32_t),
+              "the four link arrays are the head of Links");
+
 struct BeamArgs {
     const int32_t* lengths;
     const FrameHdr* hdr;
@@ -80,6 +99,9 @@ struct BeamArgs {
     double lm_alpha, lm_beta;
     int32_t B, T, V, beam;
     int32_t lm_in_lds;  // 1: table staged into LDS
+    StreamState* stream;   // streaming decode: carried state (NULL for a one-shot decode)
+    int32_t t_total;       // streaming: frames the trie and the output rows are sized for
+    int32_t out_stride;    // row length of out_tokens and of the traces
     double beam_window;  // SelectTopK's score window below the frame's best candidate; <= 0: off
     int32_t* frame_beam;        // optional trace: entries kept after each frame
     int32_t* out_token_frames;  // optional trace: frame at which each output token was appended
@@ -501,9 +523,13 @@ __global__ __launch_bounds__(kThreads) void beam_kernel(BeamArgs a) {
     float* lm_s = reinterpret_cast<float*>(dyn_lds + lm_lds_offset(V));
     constexpr bool has_lm = LM != kLmNone;
 
+    StreamState* const carried = a.stream ? a.stream + b : nullptr;  // uniform
+    const int32_t t_base = carried ? carried->frames_done : 0;
     int32_t len = a.lengths[b];
     len = len < 0 ? 0 : (len > a.T ? a.T : len);
+    if (carried && len > a.t_total - t_base) len = max(0, a.t_total - t_base);
     const int64_t g_base = (int64_t)b * a.T;
+    const int64_t trace_base = (int64_t)b * a.out_stride + t_base;
     const Survivor* rec_all = a.rec;
 
     // ---- header chunks: 32 frames x 64 B = 128 threads x 16 B ------------------------
@@ -537,6 +563,19 @@ __global__ __launch_bounds__(kThreads) void beam_kernel(BeamArgs a) {
         for (int i = tid; i < kHashSlots; i += kThreads) links[g2].ht[i] = -1;
     }
     if (tid == 0) {
+        sh_nnew = 0;
+        sh_blcount = 0;
+        sh_minD = kAllOnes;
+    }
+    if (carried) {  // the beam as the previous chunk left it
+        __syncthreads();  // the link arrays were just preset by other threads
+        const uint32_t* src = reinterpret_cast<const uint32_t*>(&carried->slab);
+        uint32_t* dst = reinterpret_cast<uint32_t*>(&slab[0]);
+        for (int i = tid; i < (int)(sizeof(BeamSlab) / 4); i += kThreads) dst[i] = src[i];
+        const uint32_t* lsrc = reinterpret_cast<const uint32_t*>(carried->par);
+        uint32_t* ldst = reinterpret_cast<uint32_t*>(&links[0]);
+        for (int i = tid; i < 4 * kMaxBeam; i += kThreads) ldst[i] = lsrc[i];
+    } else if (tid == 0) {
         BeamSlab& s0 = slab[0];
         s0.h[0] = kGolden;
         s0.hp[0] = 0;
@@ -547,9 +586,6 @@ __global__ __launch_bounds__(kThreads) void beam_kernel(BeamArgs a) {
         s0.node[0] = 0;
         s0.plen[0] = 0;
         s0.xanc[0] = 0;
-        sh_nnew = 0;
-        sh_blcount = 0;
-        sh_minD = kAllOnes;
     }
     TrieNode* trie = a.trie + (int64_t)b * trie_stride;
     const double lm_ub = has_lm ? fmax(0.0, (double)a.lm_bound[0]) : 0.0;
@@ -569,6 +605,13 @@ __global__ __launch_bounds__(kThreads) void beam_kernel(BeamArgs a) {
     double bias = 0.0;       // log-mass of the blank-only frames, common to every entry
     bool collapsed = false;  // blank-only frames since the beam was last written
     double kmax_v = 0.0, kmin_v = 0.0;  // bounds of the best / worst score (without bias)
+    if (carried) {
+        n_live = carried->n_live;
+        bias = carried->bias;
+        collapsed = carried->collapsed != 0;
+        kmax_v = carried->kmax;
+        kmin_v = carried->kmin;
+    }
 
     // statistics kept by thread 0
     uint64_t st_surv = 0, st_cand = 0, st_peak = 0, st_beam = 0, st_pass = 0, st_exact = 0,
@@ -595,7 +638,7 @@ __global__ __launch_bounds__(kThreads) void beam_kernel(BeamArgs a) {
         if (t + 1 < t_end) head_next = FLTOP_RING_HEAD(t + 1);
         if (tid == 0) st_surv += (uint64_t)K;
         if (n_live == 0) {
-            if (a.frame_beam && tid == 0) a.frame_beam[g] = 0;
+            if (a.frame_beam && tid == 0) a.frame_beam[trace_base + t] = 0;
             continue;
         }
 
@@ -612,7 +655,7 @@ __global__ __launch_bounds__(kThreads) void beam_kernel(BeamArgs a) {
                 st_cand += (uint64_t)n_live;
                 if ((uint64_t)n_live > st_peak) st_peak = (uint64_t)n_live;
                 st_beam += (uint64_t)n_live;
-                if (a.frame_beam) a.frame_beam[g] = n_live;
+                if (a.frame_beam) a.frame_beam[trace_base + t] = n_live;
             }
             PHASE_MARK(7);
             continue;
@@ -923,9 +966,11 @@ __global__ __launch_bounds__(kThreads) void beam_kernel(BeamArgs a) {
             PHASE_MARK(9);
             if (sel_s) emit_stay(fc, nxt, lkn, slot++, beam, tid, my_pb, my_pnb, my_tot);
             if (sel_0)
-                emit_ext(fc, nxt, lkn, slot++, beam, t, cD0, cI0, cT0, hh0, hv0, trie, trie_stride);
+                emit_ext(fc, nxt, lkn, slot++, beam, t_base + t, cD0, cI0, cT0, hh0, hv0, trie,
+                         trie_stride);
             if (sel_1)
-                emit_ext(fc, nxt, lkn, slot++, beam, t, cD1, cI1, cT1, hh1, hv1, trie, trie_stride);
+                emit_ext(fc, nxt, lkn, slot++, beam, t_base + t, cD1, cI1, cT1, hh1, hv1, trie,
+                         trie_stride);
         }
         for (int m = kRegCand; m < M; ++m) {  // candidates beyond the register cache
             const int e = e_first + m * kThreads;
@@ -944,8 +989,8 @@ __global__ __launch_bounds__(kThreads) void beam_kernel(BeamArgs a) {
             if (lane == 0) base = atomicAdd(&sh_nnew, __popcll(m_sel));
             base = __builtin_amdgcn_readfirstlane(base);
             if (sel)
-                emit_ext(fc, nxt, lkn, base + lanes_below(m_sel, lane), beam, t, D, se, tk, hh,
-                         have_h, trie, trie_stride);
+                emit_ext(fc, nxt, lkn, base + lanes_below(m_sel, lane), beam, t_base + t, D, se, tk,
+                         hh, have_h, trie, trie_stride);
         }
         lds_barrier();
         PHASE_MARK(5);
@@ -991,7 +1036,7 @@ __global__ __launch_bounds__(kThreads) void beam_kernel(BeamArgs a) {
         if (tid < kCoarse) hcoarse[tid] = 0u;
         if (tid == 0) {
             sh_minD = kAllOnes;
-            if (a.frame_beam) a.frame_beam[g] = n_new;
+            if (a.frame_beam) a.frame_beam[trace_base + t] = n_new;
         }
         if (big)
             for (int k = tid; k < K; k += kThreads) dense_lp[s_tok[k]] = -INFINITY;
@@ -1067,8 +1112,9 @@ __global__ __launch_bounds__(kThreads) void beam_kernel(BeamArgs a) {
     if (best >= 0) {
         int node = fin.node[best];
         int depth = fin.plen[best];
-        int32_t* dst = a.out_tokens + (int64_t)b * a.T;
-        int32_t* born = a.out_token_frames ? a.out_token_frames + (int64_t)b * a.T : nullptr;
+        int32_t* dst = a.out_tokens + (int64_t)b * a.out_stride;
+        int32_t* born =
+            a.out_token_frames ? a.out_token_frames + (int64_t)b * a.out_stride : nullptr;
         while (depth > 0) {  // uniform: node/depth are re-read from LDS after each batch
             if (tid == 0) {
                 int n = 0;
@@ -1124,7 +1170,7 @@ __global__ __launch_bounds__(kThreads) void beam_kernel(BeamArgs a) {
             a.nbest_pb[row] = (collapsed ? fin.ptot[tid] : fin.pb[tid]) + bias;
             a.nbest_pnb[row] = collapsed ? -INFINITY : fin.pnb[tid] + bias;
             int node = fin.node[tid];
-            int32_t* dst = a.nbest_tokens + row * a.T;
+            int32_t* dst = a.nbest_tokens + row * a.out_stride;
             for (int p = n - 1; p >= 0 && node > 0 && (int64_t)node < a.trie_stride; --p) {
                 const TrieNode tn = trie[node];
                 dst[p] = tn.tok;
@@ -1132,20 +1178,73 @@ __global__ __launch_bounds__(kThreads) void beam_kernel(BeamArgs a) {
             }
         }
     }
+
+    // ---- streaming: leave the beam for the next chunk -----------------------------------
+    if (carried) {
+        const uint32_t* src = reinterpret_cast<const uint32_t*>(&slab[gen]);
+        uint32_t* dst = reinterpret_cast<uint32_t*>(&carried->slab);
+        for (int i = tid; i < (int)(sizeof(BeamSlab) / 4); i += kThreads) dst[i] = src[i];
+        const uint32_t* lsrc = reinterpret_cast<const uint32_t*>(&links[gen]);
+        uint32_t* ldst = reinterpret_cast<uint32_t*>(carried->par);
+        for (int i = tid; i < 4 * kMaxBeam; i += kThreads) ldst[i] = lsrc[i];
+        if (tid == 0) {
+            carried->frames_done = t_base + len;
+            carried->n_live = n_live;
+            carried->collapsed = collapsed ? 1 : 0;
+            carried->bias = bias;
+            carried->kmax = kmax_v;
+            carried->kmin = kmin_v;
+        }
+    }
+}
+
+// A fresh stream: the empty prefix with score 0, no links, no frames seen.
+__global__ __launch_bounds__(kThreads) void stream_begin_kernel(StreamState* st, int32_t B) {
+    for (int32_t b = blockIdx.x; b < B; b += gridDim.x) {
+        StreamState* s = st + b;
+        uint32_t* words = reinterpret_cast<uint32_t*>(s);
+        for (int i = threadIdx.x; i < (int)(sizeof(StreamState) / 4); i += kThreads) words[i] = 0u;
+        __syncthreads();
+        for (int i = threadIdx.x; i < kMaxBeam; i += kThreads) {
+            s->par[i] = -1;
+            s->first_kid[i] = -1;
+            s->next_kid[i] = -1;
+        }
+        if (threadIdx.x == 0) {
+            s->n_live = 1;
+            s->slab.h[0] = kGolden;
+            s->slab.pb[0] = 0.0;
+            s->slab.pnb[0] = -INFINITY;
+            s->slab.ptot[0] = 0.0;
+            s->slab.last[0] = -1;
+        }
+        __syncthreads();
+    }
 }
 
 }  // namespace
 
+size_t stream_record_bytes() { return sizeof(StreamState); }
+
+hipError_t launch_stream_begin(void* records, int32_t B, hipStream_t stream) {
+    hipLaunchKernelGGL(stream_begin_kernel, dim3((unsigned)(B < 1024 ? B : 1024)), dim3(kThreads),
+                       0, stream, static_cast<StreamState*>(records), B);
+    return hipGetLastError();
+}
+
 hipError_t launch_beam(const int32_t* lengths, int32_t B, int32_t T, int32_t V,
-                       const fltop_params& p, const Workspace& ws, int32_t* out_tokens,
-                       int32_t* out_lengths, float* out_scores, fltop_stats* stats,
-                       hipStream_t stream) {
+                       const fltop_params& p, const Workspace& ws, const StreamSpace* carried,
+                       int32_t* out_tokens, int32_t* out_lengths, float* out_scores,
+                       fltop_stats* stats, hipStream_t stream) {
     BeamArgs a;
     a.lengths = lengths;
     a.hdr = ws.hdr;
     a.rec = ws.rec;
-    a.trie = ws.trie;
-    a.trie_stride = ws.trie_stride;
+    a.trie = carried ? carried->trie : ws.trie;
+    a.trie_stride = carried ? carried->trie_stride : ws.trie_stride;
+    a.stream = carried ? static_cast<StreamState*>(carried->records) : nullptr;
+    a.t_total = carried ? carried->t_total : T;
+    a.out_stride = carried ? carried->t_total : T;
     a.lm_table = p.lm_table;
     a.lm_bound = ws.lm_bound;
     a.lm_alpha = (double)p.lm_weight;

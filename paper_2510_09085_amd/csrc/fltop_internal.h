@@ -80,6 +80,32 @@ inline Workspace carve_workspace(void* base, int32_t B, int32_t T, int32_t V, in
     return w;
 }
 
+// Device memory of a streaming decode: one fixed-size record per utterance (the carried
+// beam), then the prefix trie for up to t_total frames.
+struct StreamSpace {
+    void* records;
+    TrieNode* trie;
+    int64_t trie_stride;  // nodes per utterance: t_total * beam + 1
+    int32_t t_total;
+    size_t bytes;
+};
+
+size_t stream_record_bytes();
+
+inline StreamSpace carve_stream(void* base, int32_t B, int32_t t_total, int32_t beam) {
+    StreamSpace s;
+    s.t_total = t_total;
+    s.trie_stride = (int64_t)t_total * beam + 1;
+    const size_t off_trie = align_up((size_t)B * stream_record_bytes(), 256);
+    s.bytes = align_up(off_trie + (size_t)B * (size_t)s.trie_stride * sizeof(TrieNode), 256);
+    char* p = static_cast<char*>(base);
+    s.records = p;
+    s.trie = p ? reinterpret_cast<TrieNode*>(p + off_trie) : nullptr;
+    return s;
+}
+
+hipError_t launch_stream_begin(void* records, int32_t B, hipStream_t stream);
+
 // Launchers (defined next to their kernels); each returns a hipError_t.
 hipError_t launch_prune(const float* logprobs, const int32_t* lengths, int32_t B, int32_t T,
                         int32_t V, float ln_r, int32_t top_n, const Workspace& ws,
@@ -94,9 +120,9 @@ hipError_t launch_unpack(const Workspace& ws, const int32_t* lengths, int32_t B,
 hipError_t launch_lm_bound(const float* lm_table, int32_t V, float lm_weight, float bonus,
                            float* out, hipStream_t stream);
 hipError_t launch_beam(const int32_t* lengths, int32_t B, int32_t T, int32_t V,
-                       const fltop_params& p, const Workspace& ws, int32_t* out_tokens,
-                       int32_t* out_lengths, float* out_scores, fltop_stats* stats,
-                       hipStream_t stream);
+                       const fltop_params& p, const Workspace& ws, const StreamSpace* carried,
+                       int32_t* out_tokens, int32_t* out_lengths, float* out_scores,
+                       fltop_stats* stats, hipStream_t stream);
 
 }  // namespace fltop
 #endif  // FLTOP_INTERNAL_H_

@@ -67,6 +67,11 @@ WORKLOADS = {
     "cfg5_bigram_lm": Workload("cfg5_bigram_lm", B=128, T=500, V=32, beam=64,
                                rel_thresholds=(0.01, 0.0), seed=1005, use_lm=True,
                                lm_weight=0.5, insertion_bonus=1.0),
+    # beyond the five base workloads: a sub-word vocabulary with a dense bigram table that no
+    # longer fits in LDS (4 MB), so LM terms are gathered from global memory
+    "ext_subword1024_lm": Workload("ext_subword1024_lm", B=128, T=400, V=1024, beam=64,
+                                   rel_thresholds=(0.01,), seed=1006, zipf_s=1.1, use_lm=True,
+                                   lm_weight=0.5, insertion_bonus=1.0),
 }
 
 

@@ -235,3 +235,24 @@ def test_option_errors_reach_the_caller(dev):
     with pytest.raises(binding.FltopError) as e:
         binding.decode(lp, ln, 4, 0.1, beam_threshold=float("nan"))
     assert e.value.status == -9
+
+
+# --------------------------------------------------------------------------- larger LM
+def test_subword_vocabulary_with_global_memory_bigram_table(dev, oracle_lib):
+    """V = 1024 with a dense bigram table (4 MB: gathered from global memory, not LDS), the
+    whole batch on the GPU in its benchmark launch shape, a sample of it in the oracle."""
+    w = synth.WORKLOADS["ext_subword1024_lm"]
+    lp, ln = synth.make_emissions(w)
+    lm = synth.make_bigram_lm(w.V)
+    got = gpu_decode(dev, lp, ln, w.beam, 0.01, lm=lm, lm_weight=w.lm_weight,
+                     insertion_bonus=w.insertion_bonus)
+    idx = list(range(0, w.B, 16))
+    want = oracle_lib.decode(lp[idx], ln[idx], w.beam, 0.01, lm_table=lm, lm_weight=w.lm_weight,
+                             insertion_bonus=w.insertion_bonus, traces=True, n_threads=8)
+    for k, b in enumerate(idx):
+        assert got["tokens"][b] == want[0][k], f"utterance {b}"
+        assert got["token_frames"][b] == want[2]["token_frames"][k]
+        np.testing.assert_array_equal(got["frame_beam"][b, :ln[b]], want[2]["frame_beam"][k, :ln[b]])
+        assert abs(float(got["scores"][b]) - float(np.float32(want[1][k]))) <= SCORE_TOL
+    assert got["stats"]["frames"] == int(ln.sum())
+    assert got["stats"]["overflow_drops"] == 0

@@ -1,0 +1,147 @@
+"""GPU parity for streaming (chunked) decoding: feeding an utterance in pieces with the beam
+carried between calls must give what the oracle gives on the whole utterance, and after
+every chunk what the oracle gives on the frames seen so far."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2510_09085_amd import binding, synth
+
+pytestmark = pytest.mark.gpu
+
+SCORE_TOL = 1e-4
+
+
+@pytest.fixture(scope="module")
+def dev():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    binding.load()
+    return torch.device("cuda:0")
+
+
+def feed_in_chunks(dev, lp, ln, chunk, beam, r, check_at=(), oracle_lib=None, okw=None, **kw):
+    B, T, V = lp.shape
+    lm = kw.pop("lm", None)
+    if lm is not None:
+        kw["lm_table"] = torch.from_numpy(np.ascontiguousarray(lm)).to(dev)
+    st = binding.Stream(B, T, chunk, V, beam, r, dev, want_traces=True, **kw)
+    totals = {k: 0 for k in ("frames", "sum_survivors", "sum_candidates", "sum_beam")}
+    peak = 0
+    for t0 in range(0, T, chunk):
+        tc = min(chunk, T - t0)
+        piece = np.ascontiguousarray(lp[:, t0:t0 + tc])
+        piece_len = np.clip(ln - t0, 0, tc).astype(np.int32)
+        st.stats.zero_()
+        st.feed(torch.from_numpy(piece).to(dev), torch.from_numpy(piece_len).to(dev))
+        torch.cuda.synchronize()
+        s = binding.stats_dict(st.stats)
+        for k in totals:
+            totals[k] += s[k]
+        peak = max(peak, s["peak_candidates"])
+        assert s["overflow_drops"] == 0
+        if t0 + tc in check_at:  # partial transcript = decode of the frames seen so far
+            seen = np.minimum(ln, t0 + tc).astype(np.int32)
+            want = oracle_lib.decode(lp[:, :t0 + tc], seen, beam, r, n_threads=4, **(okw or {}))
+            lens = st.lengths.cpu().numpy()
+            toks = st.tokens.cpu().numpy()
+            for b in range(B):
+                assert toks[b, :lens[b]].tolist() == want[0][b], f"partial at {t0 + tc}, b={b}"
+            ws = want[1].astype(np.float32)
+            assert np.all(np.abs(st.scores.cpu().numpy().astype(np.float64) - ws) <= SCORE_TOL)
+    lens = st.lengths.cpu().numpy()
+    toks = st.tokens.cpu().numpy()
+    tf = st.token_frames.cpu().numpy()
+    totals["peak_candidates"] = peak
+    return {"tokens": [toks[b, :lens[b]].tolist() for b in range(B)],
+            "token_frames": [tf[b, :lens[b]].tolist() for b in range(B)],
+            "frame_beam": st.frame_beam.cpu().numpy(), "scores": st.scores.cpu().numpy(),
+            "stats": totals}
+
+
+def check_final(got, want, ln, label):
+    toks, scores, st = want
+    for b in range(len(toks)):
+        assert got["tokens"][b] == toks[b], f"{label}: utterance {b} tokens differ"
+        assert got["token_frames"][b] == st["token_frames"][b], f"{label}: utterance {b} frames"
+        n = int(ln[b])
+        np.testing.assert_array_equal(got["frame_beam"][b, :n], st["frame_beam"][b, :n])
+        assert (got["frame_beam"][b, n:] == -1).all()
+    ws = np.asarray(scores, dtype=np.float64).astype(np.float32)
+    assert np.all(np.abs(got["scores"].astype(np.float64) - ws) <= SCORE_TOL), label
+    for key in ("frames", "sum_survivors", "sum_candidates", "peak_candidates", "sum_beam"):
+        assert got["stats"][key] == st[key], (label, key)
+
+
+@pytest.mark.parametrize("chunk", [1, 7, 32, 100, 333, 500])
+def test_chunked_decode_equals_whole_decode(dev, oracle_lib, chunk):
+    w = synth.WORKLOADS["cfg2_batch64"]
+    lp, ln = synth.make_emissions(w, utterances=range(4 if chunk == 1 else 8))
+    want = oracle_lib.decode(lp, ln, w.beam, 0.01, traces=True, n_threads=8)
+    got = feed_in_chunks(dev, lp, ln, chunk, w.beam, 0.01)
+    check_final(got, want, ln, f"chunk {chunk}")
+    # and bit-identical to the one-shot GPU decode (same arithmetic in the same order)
+    lp_d, ln_d = torch.from_numpy(lp).to(dev), torch.from_numpy(ln).to(dev)
+    one = binding.decode(lp_d, ln_d, w.beam, 0.01)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(one["scores"].cpu().numpy(), got["scores"])
+
+
+def test_streams_of_different_lengths_with_partial_transcripts(dev, oracle_lib):
+    w = synth.WORKLOADS["cfg3_varlen256"]
+    all_len = synth.make_lengths(w)
+    order = np.argsort(all_len)
+    idx = sorted({int(order[0]), int(order[1]), int(order[len(order) // 2]), int(order[-1])})
+    lp, ln = synth.make_emissions(w, pad_value=0.0, utterances=idx)
+    want = oracle_lib.decode(lp, ln, w.beam, 0.01, traces=True, n_threads=8)
+    got = feed_in_chunks(dev, lp, ln, 160, w.beam, 0.01, check_at=(160, 480, 1120),
+                         oracle_lib=oracle_lib)
+    check_final(got, want, ln, "varlen chunks of 160")
+
+
+def test_chunked_decode_with_lm_top_n_and_window(dev, oracle_lib):
+    w = synth.WORKLOADS["cfg5_bigram_lm"]
+    lp, ln = synth.make_emissions(w, utterances=range(4))
+    lm = synth.make_bigram_lm(w.V)
+    okw = dict(lm_table=lm, lm_weight=w.lm_weight, insertion_bonus=w.insertion_bonus, top_n=4,
+               beam_threshold=6.0)
+    want = oracle_lib.decode(lp, ln, w.beam, 0.007, traces=True, n_threads=4, **okw)
+    got = feed_in_chunks(dev, lp, ln, 64, w.beam, 0.007, lm=lm, lm_weight=w.lm_weight,
+                         insertion_bonus=w.insertion_bonus, top_n=4, beam_threshold=6.0,
+                         check_at=(128,), oracle_lib=oracle_lib, okw=okw)
+    check_final(got, want, ln, "lm + top-4 + window, chunks of 64")
+
+
+def test_unpruned_chunks_and_restart(dev, oracle_lib):
+    lp = synth.random_emissions(91, 2, 90, 40, flat=2.0)
+    ln = np.array([90, 61], dtype=np.int32)
+    want = oracle_lib.decode(lp, ln, 128, 0.0, traces=True, n_threads=2)
+    got = feed_in_chunks(dev, lp, ln, 25, 128, 0.0)
+    check_final(got, want, ln, "unpruned beam 128")
+    # begin() again: the same state decodes a fresh pair of streams
+    st = binding.Stream(2, 90, 45, 40, 128, 0.0, dev)
+    for rep in range(2):
+        st.begin()
+        for t0 in (0, 45):
+            piece_len = np.clip(ln - t0, 0, 45).astype(np.int32)
+            st.feed(torch.from_numpy(np.ascontiguousarray(lp[:, t0:t0 + 45])).to(dev),
+                    torch.from_numpy(piece_len).to(dev))
+        torch.cuda.synchronize()
+        lens = st.lengths.cpu().numpy()
+        toks = st.tokens.cpu().numpy()
+        for b in range(2):
+            assert toks[b, :lens[b]].tolist() == want[0][b], f"restart {rep}"
+
+
+def test_stream_argument_errors(dev):
+    assert binding.load().fltop_ctc_stream_state_bytes(0, 10, 4) == 0
+    assert binding.load().fltop_ctc_stream_state_bytes(2, 10, 500) == 0
+    st = binding.Stream(1, 8, 4, 8, 4, 0.1, dev)
+    with pytest.raises(ValueError):
+        st.feed(torch.zeros((1, 5, 8), dtype=torch.float32, device=dev),
+                torch.full((1,), 5, dtype=torch.int32, device=dev))
+    # frames beyond T_total are ignored, not written
+    for _ in range(3):
+        st.feed(torch.zeros((1, 4, 8), dtype=torch.float32, device=dev).log_softmax(-1),
+                torch.full((1,), 4, dtype=torch.int32, device=dev))
+    torch.cuda.synchronize()
+    assert int(st.stats.cpu()[0]) >= 8  # frames counted: 4 + 4 (+ 0 for the chunk beyond the end)

@@ -241,9 +241,9 @@ __host__ __device__ inline size_t lm_lds_offset(int V) {
 // What a frame header holds besides survivors 2..5 (one 32-byte LDS read).
 struct HdrHead {
     int32_t count;
-    int32_t reserved;
+    int32_t has_blank;
     float top;
-    int32_t pad;
+    uint32_t div_magic;
     Survivor s0, s1;
 };
 
@@ -266,7 +266,7 @@ struct FrameCtx {
     bool collapsed;          // blank-only frames came last: read p_b as total, p_nb as -inf
     int nb0;                 // 1 if blank survived (it is record 0 then)
     int Knb;                 // non-blank survivors
-    uint32_t div_magic;      // ceil(2^32 / Knb) for e / Knb
+    uint32_t div_magic;      // from the frame header: umulhi(e, div_magic) == e / Knb (Knb > 1)
     uint64_t Rk;             // key of an upper bound of every candidate score
     // survivors 0..5 as plain scalars (an indexed private array would live in scratch)
     int32_t t0, t1, t2, t3, t4, t5;
@@ -688,8 +688,9 @@ __global__ __launch_bounds__(THREADS) void beam_kernel(BeamArgs a) {
         fc.lk = lk;
         fc.big = big;
         fc.collapsed = collapsed;
-        fc.t0 = K > 0 ? hd.s0.tok : -1;
-        fc.t1 = K > 1 ? hd.s1.tok : -1;
+        // unused places of the inline list hold (-1, -inf), so they can be taken as they are
+        fc.t0 = hd.s0.tok;
+        fc.t1 = hd.s1.tok;
         fc.l0 = hd.s0.lp;
         fc.l1 = hd.s1.lp;
         fc.t2 = fc.t3 = fc.t4 = fc.t5 = -1;
@@ -700,18 +701,12 @@ __global__ __launch_bounds__(THREADS) void beam_kernel(BeamArgs a) {
                            f5 = full->first[5];
             fc.t2 = f2.tok;
             fc.l2 = f2.lp;
-            if (K > 3) {
-                fc.t3 = f3.tok;
-                fc.l3 = f3.lp;
-            }
-            if (K > 4) {
-                fc.t4 = f4.tok;
-                fc.l4 = f4.lp;
-            }
-            if (K > 5) {
-                fc.t5 = f5.tok;
-                fc.l5 = f5.lp;
-            }
+            fc.t3 = f3.tok;
+            fc.l3 = f3.lp;
+            fc.t4 = f4.tok;
+            fc.l4 = f4.lp;
+            fc.t5 = f5.tok;
+            fc.l5 = f5.lp;
         }
         if (tid == 0) {
             sh_nnew = 0;
@@ -729,10 +724,10 @@ __global__ __launch_bounds__(THREADS) void beam_kernel(BeamArgs a) {
         if (big) lds_barrier();
 
         PHASE_MARK(0);
-        fc.nb0 = (K > 0 && surv_tok(fc, 0) == 0) ? 1 : 0;  // records ascend: blank first
+        fc.nb0 = hd.has_blank;  // survivors ascend by token: the blank, if kept, is the first
         fc.Knb = K - fc.nb0;
-        fc.div_magic = fc.Knb > 1 ? (uint32_t)(0x100000000ull / (uint32_t)fc.Knb) + 1u : 0u;
-        const double lp_blank = lp_of(fc, 0);
+        fc.div_magic = hd.div_magic;
+        const double lp_blank = fc.nb0 ? (double)hd.s0.lp : -INFINITY;
         const int n_ext = n_live * fc.Knb;
         const int M = (n_ext + kThreads - 1) / kThreads;  // extension candidates per thread
         // the upper half of the wavefronts takes them first (the lower half has the stays)
@@ -803,8 +798,11 @@ __global__ __launch_bounds__(THREADS) void beam_kernel(BeamArgs a) {
                 if (D_stay != kAllOnes) hist_add(fc, w, D_stay, tid, -1, hfine, hcoarse);
                 if (cD0 != kAllOnes) hist_add(fc, w, cD0, cI0, cT0, hfine, hcoarse);
                 if (cD1 != kAllOnes) hist_add(fc, w, cD1, cI1, cT1, hfine, hcoarse);
-                uint64_t nearest = D_stay < cD0 ? D_stay : cD0;  // this thread's best candidate
-                nearest = cD1 < nearest ? cD1 : nearest;
+                uint64_t nearest = kAllOnes;  // this thread's best candidate (score window only)
+                if (windowed) {
+                    nearest = D_stay < cD0 ? D_stay : cD0;
+                    nearest = cD1 < nearest ? cD1 : nearest;
+                }
                 if (M > kRegCand) {
                     int n_clamp = 0;
                     for (int m = kRegCand; m < M; ++m) {
@@ -813,7 +811,7 @@ __global__ __launch_bounds__(THREADS) void beam_kernel(BeamArgs a) {
                         int se;
                         int32_t tk;
                         const uint64_t D = eval_ext<LM>(fc, e, se, tk);
-                        nearest = D < nearest ? D : nearest;
+                        if (windowed) nearest = D < nearest ? D : nearest;
                         if (D != kAllOnes)
                             hist_add_many(fc, w, D, se, tk, hfine, hcoarse, n_clamp);
                     }

@@ -23,11 +23,13 @@ constexpr int kInlineSurvivors = 6;
 
 // Per-frame header written by the prune stage (one 64-byte line).
 struct alignas(64) FrameHdr {
-    int32_t count;     // |S_t| (0 for frames at or beyond the utterance length)
-    int32_t reserved;  // 0
-    float top;         // max_v lp[t][v]
-    int32_t pad;
-    Survivor first[kInlineSurvivors];  // survivors 0..min(count,6)-1, ascending token
+    int32_t count;       // |S_t| (0 for frames at or beyond the utterance length)
+    int32_t has_blank;   // 1 if token 0 survived (it is survivor 0 then), else 0
+    float top;           // max_v lp[t][v]
+    uint32_t div_magic;  // floor((2^32 - 1) / n) + 1 for n = count - has_blank > 1, else 0:
+                         // umulhi(e, div_magic) == e / n for every e < 2^19
+    Survivor first[kInlineSurvivors];  // survivors 0..min(count,6)-1, ascending token; unused
+                                       // places hold (token -1, log-prob -inf)
 };
 static_assert(sizeof(FrameHdr) == 64, "FrameHdr must be one 64-byte line");
 

@@ -261,6 +261,13 @@ __global__ __launch_bounds__(kThreads) void prune_kernel(
                 }
             }
         }
+        // whether the blank (token 0, held by the group's first lane) survived: the search
+        // stage wants it, and the number of other survivors, ready-made
+        const int has_blank = group_sum<LPF>(lg == 0 ? (int)(keep[0] & 1u) : 0);
+        // unused places of the header's inline list read as (token -1, log-prob -inf)
+        for (int p = lg; p < 3; p += LPF)
+            reinterpret_cast<int4*>(img)[1 + p] =
+                make_int4(-1, __float_as_int(-INFINITY), -1, __float_as_int(-INFINITY));
         int total = 0;
 #pragma unroll
         for (int it = 0; it < ITERS; ++it) {
@@ -288,12 +295,13 @@ __global__ __launch_bounds__(kThreads) void prune_kernel(
             }
         }
         if (lg == LPF - 1) {
+            const uint32_t others = (uint32_t)(total - has_blank);
             int4 h;
             h.x = total;
-            h.y = 0;
+            h.y = has_blank;
             h.z = __float_as_int(m);
-            h.w = 0;
-            *reinterpret_cast<int4*>(img) = h;  // count, reserved, top, pad
+            h.w = others > 1u ? (int)(0xFFFFFFFFu / others + 1u) : 0;
+            *reinterpret_cast<int4*>(img) = h;  // count, has_blank, top, div_magic
         }
         // LDS operations of one wavefront execute in order, so the images are complete
         // for the reads below.  Frames beyond the length get no header: never read, and
@@ -335,7 +343,7 @@ __global__ __launch_bounds__(kThreads) void unpack_kernel(
     }
     struct Head {
         int32_t count;
-        int32_t reserved;
+        int32_t has_blank;
         float top;
         int32_t pad;
     };

@@ -20,7 +20,8 @@ MAX_VOCAB = 4096
 
 EXPORTS = ("fltop_ctc_workspace_bytes", "fltop_ctc_decode", "fltop_ctc_prune", "fltop_ctc_search",
            "fltop_ctc_unpack_survivors", "fltop_ctc_token_ranks", "fltop_ctc_stream_state_bytes",
-           "fltop_ctc_stream_begin", "fltop_ctc_stream_decode", "fltop_status_string")
+           "fltop_ctc_stream_begin", "fltop_ctc_stream_decode", "fltop_ctc_log_add",
+           "fltop_status_string")
 
 
 class FltopParams(ctypes.Structure):
@@ -87,6 +88,8 @@ def load():
     lib.fltop_ctc_stream_decode.restype = ctypes.c_int
     lib.fltop_ctc_stream_decode.argtypes = [vp, vp, i32, i32, i32, ctypes.POINTER(FltopParams),
                                             vp, sz, vp, sz, i32, vp, vp, vp, vp, vp]
+    lib.fltop_ctc_log_add.restype = ctypes.c_int
+    lib.fltop_ctc_log_add.argtypes = [vp, vp, vp, ctypes.c_int64, vp]
     lib.fltop_status_string.restype = ctypes.c_char_p
     lib.fltop_status_string.argtypes = [ctypes.c_int]
     _lib = lib
@@ -326,6 +329,19 @@ class Stream:
             _ptr(self.stats), _stream_handle(stream)))
         if rc != 0:
             raise FltopError(rc, "fltop_ctc_stream_decode")
+
+
+def log_add(a: torch.Tensor, b: torch.Tensor, stream=None) -> torch.Tensor:
+    """fltop_ctc_log_add on two float64 device tensors of equal size."""
+    if not (a.is_cuda and b.is_cuda and a.dtype == torch.float64 and b.dtype == torch.float64
+            and a.is_contiguous() and b.is_contiguous() and a.numel() == b.numel()):
+        raise ValueError("a and b must be contiguous float64 device tensors of one size")
+    out = torch.empty_like(a)
+    rc = int(load().fltop_ctc_log_add(_ptr(a), _ptr(b), _ptr(out), a.numel(),
+                                      _stream_handle(stream)))
+    if rc != 0:
+        raise FltopError(rc, "fltop_ctc_log_add")
+    return out
 
 
 def stats_dict(stats: torch.Tensor) -> dict:

@@ -218,6 +218,14 @@ extern "C" int fltop_ctc_token_ranks(const float* logprobs, int32_t B, int32_t T
     return e == hipSuccess ? FLTOP_OK : FLTOP_ERR_HIP;
 }
 
+extern "C" int fltop_ctc_log_add(const double* a, const double* b, double* out, int64_t n,
+                                 void* hip_stream) {
+    if (n < 0) return FLTOP_ERR_BAD_SHAPE;
+    if (n > 0 && (!a || !b || !out)) return FLTOP_ERR_NULL_POINTER;
+    hipError_t e = fltop::launch_log_add(a, b, out, n, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? FLTOP_OK : FLTOP_ERR_HIP;
+}
+
 extern "C" const char* fltop_status_string(int status) {
     switch (status) {
         case FLTOP_OK: return "ok";

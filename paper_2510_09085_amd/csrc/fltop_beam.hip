@@ -139,12 +139,71 @@ __device__ inline double key_value(uint64_t k) {
     return __longlong_as_double((long long)b);
 }
 
-__device__ inline double lse2(double a, double b) {
+// ---- log-sum-exp of two log-masses ------------------------------------------------------
+// hi + log1p(exp(lo - hi)).  The general-purpose exp and log1p of the device math library
+// take about 250 instructions for this, and two of these sit on every frame's critical path;
+// the argument ranges here are narrow (exp of a non-positive number, log1p of a number in
+// [0,1]), so both are written out for just that: exp by n ln2 + r reduction and the Taylor
+// series to r^13, log1p(u) as log(w) + c/w with w = fl(1+u), c its rounding error, log(w)
+// = k ln2 + 2 atanh(s), s = f/(2+f), series to s^25, the quotient's rounding error carried
+// along.  The term is within 2.4 ulp of the exact one (measured against 80-bit arithmetic
+// on the host), i.e. far below half an ulp of the sum it is added to.
+__device__ __forceinline__ double exp_nonpositive(double x) {
+    const double n = rint(x * 1.4426950408889634);  // log2(e)
+    // ln2 in two pieces; the upper one has 21 trailing zero bits, so n * upper is exact
+    double r = fma(-n, 0.6931471803691238, x);
+    r = fma(-n, 1.9082149292705877e-10, r);
+    double p = 1.6059043836821613e-10;  // 1/13!, then 1/12! ... 1/2!, 1, 1
+    p = fma(p, r, 2.08767569878681e-09);
+    p = fma(p, r, 2.505210838544172e-08);
+    p = fma(p, r, 2.755731922398589e-07);
+    p = fma(p, r, 2.7557319223985893e-06);
+    p = fma(p, r, 2.48015873015873e-05);
+    p = fma(p, r, 0.0001984126984126984);
+    p = fma(p, r, 0.001388888888888889);
+    p = fma(p, r, 0.008333333333333333);
+    p = fma(p, r, 0.041666666666666664);
+    p = fma(p, r, 0.16666666666666666);
+    p = fma(p, r, 0.5);
+    p = fma(p, r, 1.0);
+    p = fma(p, r, 1.0);
+    return ldexp(p, (int)n);  // underflows to 0 for very negative x, which is what is wanted
+}
+
+__device__ __forceinline__ double log1p_unit(double u) {  // 0 <= u <= 1
+    const double w = 1.0 + u;
+    const double c = u - (w - 1.0);  // what the addition lost
+    const bool upper = w > 1.4142135623730951;
+    const double f = upper ? fma(w, 0.5, -1.0) : w - 1.0;  // exact; w / 2^k = 1 + f
+    const double den = 2.0 + f;
+    const double s = f / den;
+    const double s_lo = fma(-s, den, f) * __builtin_amdgcn_rcp(den);
+    const double z = s * s;
+    double q = 0.08;  // 2/25, then 2/23 ... 2/3
+    q = fma(q, z, 0.08695652173913043);
+    q = fma(q, z, 0.09523809523809523);
+    q = fma(q, z, 0.10526315789473684);
+    q = fma(q, z, 0.11764705882352941);
+    q = fma(q, z, 0.13333333333333333);
+    q = fma(q, z, 0.15384615384615385);
+    q = fma(q, z, 0.18181818181818182);
+    q = fma(q, z, 0.2222222222222222);
+    q = fma(q, z, 0.2857142857142857);
+    q = fma(q, z, 0.4);
+    q = fma(q, z, 0.6666666666666666);
+    const double cw = (upper ? 0.5 * c : c) * __builtin_amdgcn_rcp(1.0 + f);  // c / w
+    double tail = fma(s * z, q, 2.0 * s_lo + cw);
+    if (upper) tail += 1.9082149292705877e-10;
+    const double body = 2.0 * s + tail;
+    return upper ? 0.6931471803691238 + body : body;
+}
+
+__device__ __forceinline__ double lse2(double a, double b) {
     if (a == -INFINITY) return b;
     if (b == -INFINITY) return a;
     const double hi = a > b ? a : b;
     const double lo = a > b ? b : a;
-    return hi + log1p(exp(lo - hi));
+    return hi + log1p_unit(exp_nonpositive(lo - hi));
 }
 
 __device__ inline int lanes_below(uint64_t mask, int lane) {
@@ -1243,7 +1302,24 @@ __global__ __launch_bounds__(kThreadsSmall) void stream_begin_kernel(StreamState
     }
 }
 
+// The search stage's log-sum-exp, element-wise over two arrays (for checking its rounding).
+__global__ __launch_bounds__(256) void log_add_kernel(const double* __restrict__ a,
+                                                      const double* __restrict__ b,
+                                                      double* __restrict__ out, int64_t n) {
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256)
+        out[i] = lse2(a[i], b[i]);
+}
+
 }  // namespace
+
+hipError_t launch_log_add(const double* a, const double* b, double* out, int64_t n,
+                          hipStream_t stream) {
+    if (n <= 0) return hipSuccess;
+    const int64_t blocks = (n + 255) / 256;
+    hipLaunchKernelGGL(log_add_kernel, dim3((unsigned)(blocks < 4096 ? blocks : 4096)), dim3(256),
+                       0, stream, a, b, out, n);
+    return hipGetLastError();
+}
 
 size_t stream_record_bytes() { return sizeof(StreamState); }
 

@@ -107,6 +107,8 @@ inline StreamSpace carve_stream(void* base, int32_t B, int32_t t_total, int32_t 
 }
 
 hipError_t launch_stream_begin(void* records, int32_t B, hipStream_t stream);
+hipError_t launch_log_add(const double* a, const double* b, double* out, int64_t n,
+                          hipStream_t stream);
 
 // Launchers (defined next to their kernels); each returns a hipError_t.
 hipError_t launch_prune(const float* logprobs, const int32_t* lengths, int32_t B, int32_t T,

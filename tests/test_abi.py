@@ -134,3 +134,50 @@ def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "nope.so"))
     with pytest.raises(FileNotFoundError):
         binding.load()
+
+
+def test_stream_entry_points_validate_before_any_launch(lib):
+    fake = ctypes.c_void_p(256 * 4096)
+    p = binding.FltopParams()
+    p.beam = 8
+    p.rel_threshold = 0.01
+    B, Tc, Ttot, V = 2, 10, 100, 32
+    ws_need = binding.workspace_bytes(B, Tc, V, 8)
+    st_need = lib.fltop_ctc_stream_state_bytes(B, Ttot, 8)
+    assert st_need > 0 and st_need % 256 == 0
+    # the state holds the trie for T_total frames: 16 bytes per (frame, beam slot)
+    assert st_need >= B * Ttot * 8 * 16
+    assert lib.fltop_ctc_stream_state_bytes(B, Ttot, 8) < lib.fltop_ctc_stream_state_bytes(B, 2 * Ttot, 8)
+    assert lib.fltop_ctc_stream_state_bytes(0, Ttot, 8) == 0
+    assert lib.fltop_ctc_stream_state_bytes(B, 0, 8) == 0
+    assert lib.fltop_ctc_stream_state_bytes(B, Ttot, binding.MAX_BEAM + 1) == 0
+
+    assert lib.fltop_ctc_stream_begin(None, st_need, B, Ttot, 8, None) == -1
+    assert lib.fltop_ctc_stream_begin(fake, st_need - 1, B, Ttot, 8, None) == -5
+    assert lib.fltop_ctc_stream_begin(ctypes.c_void_p(256 * 4096 + 16), st_need, B, Ttot, 8, None) == -8
+    assert lib.fltop_ctc_stream_begin(fake, st_need, B, Ttot, 0, None) == -3
+
+    def call(lp=fake, ln=fake, Tchunk=Tc, params=p, ws=fake, ws_bytes=ws_need, st=fake,
+             st_bytes=st_need, total=Ttot, tok=fake):
+        return lib.fltop_ctc_stream_decode(lp, ln, B, Tchunk, V,
+                                           ctypes.byref(params) if params else None, ws, ws_bytes,
+                                           st, st_bytes, total, tok, fake, fake, None, None)
+
+    assert call(lp=None) == -1
+    assert call(ln=None) == -1
+    assert call(params=None) == -1
+    assert call(tok=None) == -1
+    assert call(ws=None) == -1
+    assert call(st=None) == -1
+    assert call(Tchunk=0) == -2
+    assert call(total=Tc - 1) == -2          # a chunk longer than the whole stream
+    assert call(ws_bytes=ws_need - 1) == -5
+    assert call(st_bytes=st_need - 1) == -5
+    assert call(st=ctypes.c_void_p(256 * 4096 + 64)) == -8
+    q = binding.FltopParams()
+    q.beam = 8
+    q.rel_threshold = 1.5
+    assert call(params=q) == -4
+    q.rel_threshold = 0.5
+    q.top_n = -1
+    assert call(params=q) == -9

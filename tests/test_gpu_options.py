@@ -256,3 +256,37 @@ def test_subword_vocabulary_with_global_memory_bigram_table(dev, oracle_lib):
         assert abs(float(got["scores"][b]) - float(np.float32(want[1][k]))) <= SCORE_TOL
     assert got["stats"]["frames"] == int(ln.sum())
     assert got["stats"]["overflow_drops"] == 0
+
+
+# --------------------------------------------------------------------------- log-sum-exp
+def test_log_add_against_extended_precision(dev):
+    """The search stage's own log-sum-exp against numpy's in 80-bit arithmetic: the term
+    log1p(exp(min - max)) within 2.5 ulp of itself, plus the half ulp of the final addition."""
+    rng = np.random.default_rng(5)
+    n = 200000
+    a = -rng.random(n) * 400.0
+    gap = np.concatenate([rng.random(n // 4) * 45.0, rng.random(n // 4) * 2.0,
+                          np.ldexp(rng.random(n // 4), -rng.integers(0, 60, n // 4)),
+                          30.0 + rng.random(n - 3 * (n // 4)) * 600.0])
+    b = a - gap
+    swap = rng.random(n) < 0.5
+    a, b = np.where(swap, b, a), np.where(swap, a, b)
+    a[:50] = -np.inf
+    b[25:75] = -np.inf
+    a[100:110] = b[100:110]  # equal operands: max + ln 2
+    got = binding.log_add(torch.from_numpy(a).to(dev), torch.from_numpy(b).to(dev)).cpu().numpy()
+    with np.errstate(invalid="ignore"):
+        ref = np.logaddexp(a.astype(np.longdouble), b.astype(np.longdouble))
+        term = np.log1p(np.exp(-np.abs(a.astype(np.longdouble) - b.astype(np.longdouble))))
+    both_inf = np.isneginf(got) & np.isneginf(ref.astype(np.float64))
+    assert both_inf[25:50].all() and not np.isnan(got).any()
+    fin = np.isfinite(a) & np.isfinite(b)
+    bound = 0.5 * np.spacing(np.abs(ref[fin].astype(np.float64))) + \
+        2.5 * np.spacing(term[fin].astype(np.float64))
+    err = np.abs((got[fin].astype(np.longdouble) - ref[fin]).astype(np.float64))
+    assert (err <= bound).all(), float((err / bound).max())
+    np.testing.assert_array_equal(got[:25], b[:25])   # -inf is the neutral element
+    np.testing.assert_array_equal(got[50:75], a[50:75])
+    # symmetric in its operands, bit for bit
+    back = binding.log_add(torch.from_numpy(b).to(dev), torch.from_numpy(a).to(dev)).cpu().numpy()
+    np.testing.assert_array_equal(got, back)

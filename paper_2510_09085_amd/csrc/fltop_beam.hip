@@ -24,10 +24,14 @@
 //  - frames whose only survivor is blank change no prefix and no order: their
 //    log-prob goes into one per-utterance offset (scores in LDS are relative to
 //    it) and a flag says that p_b = total, p_nb = -inf holds for every entry;
-//    such a frame touches neither the beam nor a barrier;
-//  - frames with at most six survivors keep them in registers;
+//    such a frame touches neither the beam nor a barrier, and a run of them is
+//    consumed at once (the frames of a chunk are classified together);
+//  - frames with at most six survivors keep them in registers; what the prune
+//    stage can say about a frame by itself (blank kept?, the division constant
+//    that maps a candidate index to its beam entry) comes with the header;
 //  - "stay" candidates (which need the log-sum-exps) and extension candidates are
-//    mapped to different wavefronts so that they are evaluated side by side.
+//    mapped to different wavefronts so that they are evaluated side by side, and
+//    the end-of-frame clean-up is done by the wavefronts that have no links to set.
 #include "fltop_internal.h"
 
 namespace fltop {
@@ -707,7 +711,6 @@ __global__ __launch_bounds__(THREADS) void beam_kernel(BeamArgs a) {
             wave_inclusive_scan(inside ? hh.count : 0), kWave - 1);
         if (tid == 0) st_surv += (uint64_t)chunk_survivors;
     }
-    // header of the next frame that is not blank-only, read ahead of its turn
 
     for (int t = c * kChunk; t < t_end; ++t) {
         const int64_t g = g_base + t;
@@ -733,7 +736,7 @@ __global__ __launch_bounds__(THREADS) void beam_kernel(BeamArgs a) {
             PHASE_MARK(7);
             continue;
         }
-        const HdrHead hd = FLTOP_RING_HEAD(t);
+        const FrameHdr hd = ring[t % kChunk];  // all 64 bytes in one round trip
         const int K = hd.count;
 
         BeamSlab* const cur = &slab[gen];
@@ -748,25 +751,18 @@ __global__ __launch_bounds__(THREADS) void beam_kernel(BeamArgs a) {
         fc.big = big;
         fc.collapsed = collapsed;
         // unused places of the inline list hold (-1, -inf), so they can be taken as they are
-        fc.t0 = hd.s0.tok;
-        fc.t1 = hd.s1.tok;
-        fc.l0 = hd.s0.lp;
-        fc.l1 = hd.s1.lp;
-        fc.t2 = fc.t3 = fc.t4 = fc.t5 = -1;
-        fc.l2 = fc.l3 = fc.l4 = fc.l5 = -INFINITY;
-        if (!big && K > 2) {
-            const FrameHdr* full = &ring[t % kChunk];
-            const Survivor f2 = full->first[2], f3 = full->first[3], f4 = full->first[4],
-                           f5 = full->first[5];
-            fc.t2 = f2.tok;
-            fc.l2 = f2.lp;
-            fc.t3 = f3.tok;
-            fc.l3 = f3.lp;
-            fc.t4 = f4.tok;
-            fc.l4 = f4.lp;
-            fc.t5 = f5.tok;
-            fc.l5 = f5.lp;
-        }
+        fc.t0 = hd.first[0].tok;
+        fc.l0 = hd.first[0].lp;
+        fc.t1 = hd.first[1].tok;
+        fc.l1 = hd.first[1].lp;
+        fc.t2 = hd.first[2].tok;
+        fc.l2 = hd.first[2].lp;
+        fc.t3 = hd.first[3].tok;
+        fc.l3 = hd.first[3].lp;
+        fc.t4 = hd.first[4].tok;
+        fc.l4 = hd.first[4].lp;
+        fc.t5 = hd.first[5].tok;
+        fc.l5 = hd.first[5].lp;
         if (tid == 0) {
             sh_nnew = 0;
             sh_blcount = 0;
@@ -786,7 +782,7 @@ __global__ __launch_bounds__(THREADS) void beam_kernel(BeamArgs a) {
         fc.nb0 = hd.has_blank;  // survivors ascend by token: the blank, if kept, is the first
         fc.Knb = K - fc.nb0;
         fc.div_magic = hd.div_magic;
-        const double lp_blank = fc.nb0 ? (double)hd.s0.lp : -INFINITY;
+        const double lp_blank = fc.nb0 ? (double)hd.first[0].lp : -INFINITY;
         const int n_ext = n_live * fc.Knb;
         const int M = (n_ext + kThreads - 1) / kThreads;  // extension candidates per thread
         // the upper half of the wavefronts takes them first (the lower half has the stays)
@@ -1103,16 +1099,20 @@ __global__ __launch_bounds__(THREADS) void beam_kernel(BeamArgs a) {
             }
         }
         PHASE_MARK(10);
+        // header of the next full-path frame: issued now, awaited with the barrier below
         // housekeeping behind this frame's last readers: the old generation's links
-        // (next used as the new generation of the following frame), the histogram, and
-        // the staged survivors
-        for (int i = tid; i < kHashSlots; i += kThreads) lk->ht[i] = -1;
-        if (tid < kMaxBeam) {
-            lk->first_kid[tid] = -1;
-            lk->kidmask[tid] = 0u;
+        // (next used as the new generation of the following frame) and the histogram.
+        // The upper half of the threads does it: the lower half has just done the links.
+        if (tid >= kThreads / 2) {
+            const int u = tid - kThreads / 2;
+            for (int i = u; i < kHashSlots; i += kThreads / 2) lk->ht[i] = -1;
+            for (int i = u; i < kMaxBeam; i += kThreads / 2) {
+                lk->first_kid[i] = -1;
+                lk->kidmask[i] = 0u;
+            }
+            for (int i = u; i < kFine; i += kThreads / 2) hfine[i] = 0u;
+            if (u < kCoarse) hcoarse[u] = 0u;
         }
-        for (int i = tid; i < kFine; i += kThreads) hfine[i] = 0u;
-        if (tid < kCoarse) hcoarse[tid] = 0u;
         if (tid == 0) {
             sh_minD = kAllOnes;
             if (a.frame_beam) a.frame_beam[trace_base + t] = n_new;

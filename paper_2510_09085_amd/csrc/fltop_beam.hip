@@ -8,9 +8,12 @@
 // k"; candidates are held in registers (or recomputed when there are more than
 // the registers hold), never written to memory.  An extension i+s can only
 // coincide with a prefix that is already in the beam (a prefix has one parent),
-// so merging is done from the side of that beam entry: it finds its parent
-// through an LDS hash table and adds the parent's extension mass to its own
-// p_nb; the extension itself is then skipped.  Every log-sum-exp has two operands.
+// so merging is done from the side of that beam entry: it knows its parent's
+// place in the beam and adds the parent's extension mass to its own p_nb; the
+// extension itself is then skipped.  Every log-sum-exp has two operands.  The
+// parent links are carried from frame to frame through a map "old place -> new
+// place" of the entries that stay; only a prefix whose parent was absent looks
+// it up in a small LDS hash table of the prefixes that entered in this frame.
 //
 // Top-`beam` selection works on an order-preserving 64-bit image of the fp64
 // score: a two-level histogram over the distance to an upper bound locates the
@@ -71,7 +74,8 @@ struct Links {
     int32_t first_kid[kMaxBeam];
     int32_t next_kid[kMaxBeam];
     uint32_t kidmask[kMaxBeam];  // bit (token & 31) set for every child in the beam
-    int32_t ht[kHashSlots];      // open addressing: slot -> beam index, keyed by prefix hash
+    int32_t ht[kHashSlots];      // open addressing: slot -> beam index of a prefix that entered
+                                 // in this generation's frame, keyed by prefix hash
 };
 
 // What a streaming (chunked) decode carries from one call to the next, per utterance: the
@@ -514,11 +518,17 @@ __device__ __forceinline__ void publish_hash(Links* lkn, uint64_t hh, int slot) 
 }
 
 // Entry `se` keeps its prefix: copy it into `slot` of the next beam with its new masses.
-__device__ __forceinline__ void emit_stay(const FrameCtx& f, BeamSlab* nxt, Links* lkn, int slot,
-                                          int beam, int se, double pb, double pnb, double tot) {
+__device__ __forceinline__ void emit_stay(const FrameCtx& f, BeamSlab* nxt, Links* lkn,
+                                          int32_t* newslot, int slot, int beam, int se, double pb,
+                                          double pnb, double tot) {
     if (slot >= beam) return;  // only after a hash collision
     const BeamSlab* cur = f.cur;
     const uint64_t hh = cur->h[se];
+    // where this entry went, and where its parent was (or -2: the parent was not in the
+    // beam, so it can only be in the new one as a fresh extension)
+    const int32_t par_old = f.lk->par[se];
+    newslot[se] = slot;
+    lkn->par[slot] = par_old >= 0 ? par_old : -2;
     nxt->h[slot] = hh;
     nxt->hp[slot] = cur->hp[se];
     nxt->pb[slot] = pb;
@@ -528,7 +538,6 @@ __device__ __forceinline__ void emit_stay(const FrameCtx& f, BeamSlab* nxt, Link
     nxt->node[slot] = cur->node[se];
     nxt->plen[slot] = cur->plen[se];
     nxt->xanc[slot] = cur->xanc[se];
-    publish_hash(lkn, hh, slot);
 }
 
 // Entry `se` extended by token `tk` becomes a new prefix in `slot`; its trie node id is
@@ -559,6 +568,7 @@ __device__ __forceinline__ void emit_ext(const FrameCtx& f, BeamSlab* nxt, Links
     tn.tok = tk;
     tn.depth = depth;
     if ((int64_t)node < trie_stride) trie[node] = tn;
+    lkn->par[slot] = se;  // the parent's place in the old beam
     publish_hash(lkn, hh, slot);
 }
 
@@ -574,6 +584,7 @@ __global__ __launch_bounds__(THREADS) void beam_kernel(BeamArgs a) {
     __shared__ uint64_t sh_selD, sh_selH, sh_kbest;
     __shared__ uint64_t sh_minD;  // smallest distance (= best score) among a frame's candidates
     __shared__ int32_t sh_nnew, sh_blcount, sh_best;
+    __shared__ int32_t newslot[kMaxBeam];  // old beam index -> new beam index of an entry that stays
     extern __shared__ __align__(16) unsigned char dyn_lds[];
 
     const int tid = threadIdx.x;
@@ -767,6 +778,7 @@ __global__ __launch_bounds__(THREADS) void beam_kernel(BeamArgs a) {
             sh_nnew = 0;
             sh_blcount = 0;
         }
+        for (int i = tid - kThreads / 2; i >= 0 && i < kMaxBeam; i += kThreads / 2) newslot[i] = -1;
         if (big) {
             const Survivor* recs = rec_all + g * (int64_t)V;
             const FrameHdr* full = &ring[t % kChunk];
@@ -1039,7 +1051,7 @@ __global__ __launch_bounds__(THREADS) void beam_kernel(BeamArgs a) {
             }
             int slot = base + incl - cnt;
             PHASE_MARK(9);
-            if (sel_s) emit_stay(fc, nxt, lkn, slot++, beam, tid, my_pb, my_pnb, my_tot);
+            if (sel_s) emit_stay(fc, nxt, lkn, newslot, slot++, beam, tid, my_pb, my_pnb, my_tot);
             if (sel_0)
                 emit_ext(fc, nxt, lkn, slot++, beam, t_base + t, cD0, cI0, cT0, hh0, hv0, trie,
                          trie_stride);
@@ -1079,7 +1091,10 @@ __global__ __launch_bounds__(THREADS) void beam_kernel(BeamArgs a) {
         if (tid == 0) st_beam += (uint64_t)n_new;
         if (tid < n_new) {
             int p = -1;
-            if (nxt->plen[tid] > 0) {
+            const int32_t code = lkn->par[tid];
+            if (code >= 0) {
+                p = newslot[code];  // the parent was in the old beam: did it stay, and where
+            } else if (nxt->plen[tid] > 0) {
                 const uint64_t want = nxt->hp[tid];
                 uint32_t hs = (uint32_t)want & (kHashSlots - 1);
                 for (int probe = 0; probe < kHashSlots; ++probe) {
@@ -1099,7 +1114,6 @@ __global__ __launch_bounds__(THREADS) void beam_kernel(BeamArgs a) {
             }
         }
         PHASE_MARK(10);
-        // header of the next full-path frame: issued now, awaited with the barrier below
         // housekeeping behind this frame's last readers: the old generation's links
         // (next used as the new generation of the following frame) and the histogram.
         // The upper half of the threads does it: the lower half has just done the links.

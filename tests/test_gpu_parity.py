@@ -311,3 +311,47 @@ def test_workload_cfg4_unpruned(dev, oracle_lib):
 def test_workload_cfg5(dev, oracle_lib, r):
     _check_workload(dev, oracle_lib, "cfg5_bigram_lm", r,
                     list(range(0, 128, 8)) if r > 0 else [0, 64])
+
+
+# --------------------------------------------------------------------------- size limits
+def test_largest_vocabulary_and_beam(dev, oracle_lib):
+    """V = FLTOP_MAX_VOCAB, beam = FLTOP_MAX_BEAM: every lane chunk of the prune stage and every
+    beam slot of the search stage is in use."""
+    V, beam = binding.MAX_VOCAB, binding.MAX_BEAM
+    lp = synth.random_emissions(4096, 2, 12, V, flat=3.0)
+    ln = np.array([12, 7], dtype=np.int32)
+    for r in (0.0, 0.002):
+        want = oracle_lib.decode(lp, ln, beam, r, n_threads=2)
+        got = gpu_decode(dev, lp, ln, beam, r)
+        assert_parity(got, want[0], want[1], want[2], f"V{V} beam{beam} r{r}")
+    lp_d = torch.from_numpy(lp).to(dev)
+    ln_d = torch.from_numpy(ln).to(dev)
+    ws = binding.prune(lp_d, ln_d, beam, 0.0)
+    counts = binding.unpack_survivors(ws, ln_d, 2, 12, V, beam)[0].cpu().numpy()
+    assert (counts[:12] == V).all() and (counts[12:19] == V).all() and (counts[19:] == 0).all()
+
+
+def test_more_utterances_than_one_grid_dimension_holds(dev, oracle_lib):
+    """B above 65535: the prune stage walks the utterances with a grid stride."""
+    B, T, V, beam = 66000, 3, 4, 4
+    lp = synth.random_emissions(99, 8, T, V, flat=1.0)
+    big = np.ascontiguousarray(np.tile(lp, (B // 8, 1, 1)))
+    ln = np.full(B, T, dtype=np.int32)
+    ln[1::8] = 2
+    ln[5::8] = 0
+    got = gpu_decode(dev, big, ln, beam, 0.05)
+    want = oracle_lib.decode(big[:8], ln[:8], beam, 0.05)
+    for b in list(range(16)) + list(range(B - 16, B)) + [65535, 65536, 65537]:
+        assert got["tokens"][b] == want[0][b % 8], f"utterance {b}"
+        ws = np.float32(want[1][b % 8])
+        assert abs(float(got["scores"][b]) - float(ws)) <= SCORE_TOL
+    assert got["stats"]["frames"] == int(ln.sum())
+
+
+def test_all_utterances_empty(dev, oracle_lib):
+    lp = np.full((3, 5, 8), np.nan, dtype=np.float32)
+    ln = np.zeros(3, dtype=np.int32)
+    got = gpu_decode(dev, lp, ln, 8, 0.01)
+    assert got["tokens"] == [[], [], []]
+    assert (got["scores"] == 0.0).all()
+    assert got["stats"]["frames"] == 0 and got["stats"]["sum_candidates"] == 0

@@ -69,7 +69,7 @@ struct BeamSlab {
 };
 
 // parent / children links of one beam generation
-struct Links {
+struct alignas(16) Links {
     int32_t par[kMaxBeam];
     int32_t first_kid[kMaxBeam];
     int32_t next_kid[kMaxBeam];
@@ -577,14 +577,14 @@ __global__ __launch_bounds__(THREADS) void beam_kernel(BeamArgs a) {
     constexpr int kThreads = THREADS;
     __shared__ BeamSlab slab[2];
     __shared__ Links links[2];
-    __shared__ uint32_t hfine[kFine];
-    __shared__ uint32_t hcoarse[kCoarse];
+    __shared__ __align__(16) uint32_t hfine[kFine];
+    __shared__ __align__(16) uint32_t hcoarse[kCoarse];
     __shared__ uint64_t bl_D[kExactCap], bl_h[kExactCap];
     __shared__ FrameHdr ring[kChunk];
     __shared__ uint64_t sh_selD, sh_selH, sh_kbest;
     __shared__ uint64_t sh_minD;  // smallest distance (= best score) among a frame's candidates
     __shared__ int32_t sh_nnew, sh_blcount, sh_best;
-    __shared__ int32_t newslot[kMaxBeam];  // old beam index -> new beam index of an entry that stays
+    __shared__ __align__(16) int32_t newslot[kMaxBeam];  // old beam index -> new beam index of an entry that stays
     extern __shared__ __align__(16) unsigned char dyn_lds[];
 
     const int tid = threadIdx.x;
@@ -778,7 +778,8 @@ __global__ __launch_bounds__(THREADS) void beam_kernel(BeamArgs a) {
             sh_nnew = 0;
             sh_blcount = 0;
         }
-        for (int i = tid - kThreads / 2; i >= 0 && i < kMaxBeam; i += kThreads / 2) newslot[i] = -1;
+        if (tid >= kThreads / 2 && tid - kThreads / 2 < kMaxBeam / 4)
+            reinterpret_cast<int4*>(newslot)[tid - kThreads / 2] = make_int4(-1, -1, -1, -1);
         if (big) {
             const Survivor* recs = rec_all + g * (int64_t)V;
             const FrameHdr* full = &ring[t % kChunk];
@@ -1118,14 +1119,18 @@ __global__ __launch_bounds__(THREADS) void beam_kernel(BeamArgs a) {
         // (next used as the new generation of the following frame) and the histogram.
         // The upper half of the threads does it: the lower half has just done the links.
         if (tid >= kThreads / 2) {
+            // 16 bytes per store
             const int u = tid - kThreads / 2;
-            for (int i = u; i < kHashSlots; i += kThreads / 2) lk->ht[i] = -1;
-            for (int i = u; i < kMaxBeam; i += kThreads / 2) {
-                lk->first_kid[i] = -1;
-                lk->kidmask[i] = 0u;
+            const int4 ones = make_int4(-1, -1, -1, -1), zeros = make_int4(0, 0, 0, 0);
+            for (int i = u; i < kHashSlots / 4; i += kThreads / 2)
+                reinterpret_cast<int4*>(lk->ht)[i] = ones;
+            for (int i = u; i < kMaxBeam / 4; i += kThreads / 2) {
+                reinterpret_cast<int4*>(lk->first_kid)[i] = ones;
+                reinterpret_cast<int4*>(lk->kidmask)[i] = zeros;
             }
-            for (int i = u; i < kFine; i += kThreads / 2) hfine[i] = 0u;
-            if (u < kCoarse) hcoarse[u] = 0u;
+            for (int i = u; i < kFine / 4; i += kThreads / 2)
+                reinterpret_cast<int4*>(hfine)[i] = zeros;
+            if (u < kCoarse / 4) reinterpret_cast<int4*>(hcoarse)[u] = zeros;
         }
         if (tid == 0) {
             sh_minD = kAllOnes;

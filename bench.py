@@ -189,6 +189,8 @@ def paper_arms(torch, binding, job, window):
     window of SelectTopK at `window`; per arm the decode time, the hypotheses kept per time
     step (Sec. 4.4) and, for the all-token arm, how often the decoded tokens sat at each
     position of their frame's descending emission order (Sec. 4.1)."""
+    import numpy as np
+
     w = job.w
     dev = job.ln.device
     frame_beam = torch.full((w.B, w.T), -1, dtype=torch.int32, device=dev)
@@ -207,7 +209,7 @@ def paper_arms(torch, binding, job, window):
         st = job.stats_of(p)
         fb = frame_beam.cpu().numpy()
         live = fb[fb >= 0]
-        q = [float(x) for x in __import__("numpy").percentile(live, [25, 50, 75])]
+        q = [float(x) for x in np.percentile(live, [25, 50, 75])]
         arm = {"arm": name, "top_n": n, "rel_threshold": r, "beam_threshold": window,
                "ms": round(avg, 4), "frames_per_s": round(job.frames / (avg * 1e-3), 1),
                "stage_us": {"prune": round(sum(prune_ms) / len(prune_ms) * 1e3, 2),

@@ -468,6 +468,12 @@ def main():
         #      tighter one that actually bites at this beam size
         result["paper_arms"] = {"window_25": paper_arms(torch, binding, job, 25.0),
                                 "window_6": paper_arms(torch, binding, job, 6.0)}
+        # ... and with the largest beam the library takes (the paper's baseline uses 1000)
+        import dataclasses
+        wide_job = Job(torch, binding, synth, dataclasses.replace(w, beam=binding.MAX_BEAM), dev)
+        result["paper_arms"][f"beam{binding.MAX_BEAM}_window_25"] = paper_arms(
+            torch, binding, wide_job, 25.0)
+        del wide_job
         result["batch_scaling"] = batch_scaling(torch, binding, job, r)
         result["paper_context"] = ("paper reports 10.5x runtime speedup and 2.78x fewer beams "
                                    "(FLToP N=4,R=0.007 vs all-32-token baseline) for a CPU "

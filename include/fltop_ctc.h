@@ -61,7 +61,7 @@ extern "C" {
 #define FLTOP_ERR_ALIGNMENT      -8  /* workspace not 256-byte aligned                      */
 #define FLTOP_ERR_BAD_OPTION     -9  /* top_n < 0, or beam_threshold NaN                    */
 
-#define FLTOP_MAX_BEAM   128
+#define FLTOP_MAX_BEAM   512
 #define FLTOP_MAX_VOCAB  4096
 
 /* Decoder settings (host POD, read during the call only; zero-initialise it, then set

@@ -15,7 +15,7 @@ import torch
 _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("FLTOP_CTC_LIB") or os.path.join(_PKG, "libfltop_ctc.so")
 
-MAX_BEAM = 128
+MAX_BEAM = 512
 MAX_VOCAB = 4096
 
 EXPORTS = ("fltop_ctc_workspace_bytes", "fltop_ctc_decode", "fltop_ctc_prune", "fltop_ctc_search",

@@ -43,8 +43,11 @@ namespace {
 constexpr int kThreadsSmall = 256;  // workgroup size for small vocabularies
 constexpr int kThreadsLarge = 512;  // and for large ones (see launch_beam)
 constexpr int kWave = 64;
-constexpr int kMaxBeam = FLTOP_MAX_BEAM;
-constexpr int kHashSlots = 4 * kMaxBeam;
+// The beam lives in LDS, so its capacity is a compile-time size: kernels are built for a
+// small one (which keeps several workgroups per CU for large batches) and for the largest.
+constexpr int kBeamSmall = 128;
+constexpr int kBeamLarge = FLTOP_MAX_BEAM;
+static_assert(kBeamLarge == 512, "the LDS budget below is worked out for 512 entries");
 constexpr int kFine = 1024;  // histogram bins
 constexpr int kCoarse = 64;  // one per lane; a coarse bin covers 16 fine bins
 constexpr int kExactCap = 64;
@@ -56,45 +59,50 @@ constexpr int kWaypoints = 256;
 constexpr uint64_t kGolden = 0x9E3779B97F4A7C15ull;
 constexpr uint64_t kAllOnes = ~0ull;
 
+template <int MB>
 struct BeamSlab {
-    uint64_t h[kMaxBeam];   // prefix hash
-    uint64_t hp[kMaxBeam];  // parent prefix hash (unused when plen == 0)
-    double pb[kMaxBeam];
-    double pnb[kMaxBeam];
-    double ptot[kMaxBeam];
-    int32_t last[kMaxBeam];  // last token, -1 for the empty prefix
-    int32_t node[kMaxBeam];  // trie node of the prefix
-    int32_t plen[kMaxBeam];  // prefix length
-    int32_t xanc[kMaxBeam];  // trie node of the ancestor at depth 8*floor(plen/8)
+    uint64_t h[MB];   // prefix hash
+    uint64_t hp[MB];  // parent prefix hash (unused when plen == 0)
+    double pb[MB];
+    double pnb[MB];
+    double ptot[MB];
+    int32_t last[MB];  // last token, -1 for the empty prefix
+    int32_t node[MB];  // trie node of the prefix
+    int32_t plen[MB];  // prefix length
+    int32_t xanc[MB];  // trie node of the ancestor at depth 8*floor(plen/8)
 };
 
 // parent / children links of one beam generation
+template <int MB>
 struct alignas(16) Links {
-    int32_t par[kMaxBeam];
-    int32_t first_kid[kMaxBeam];
-    int32_t next_kid[kMaxBeam];
-    uint32_t kidmask[kMaxBeam];  // bit (token & 31) set for every child in the beam
-    int32_t ht[kHashSlots];      // open addressing: slot -> beam index of a prefix that entered
+    int32_t par[MB];
+    int32_t first_kid[MB];
+    int32_t next_kid[MB];
+    uint32_t kidmask[MB];  // bit (token & 31) set for every child in the beam
+    int32_t ht[4 * MB];      // open addressing: slot -> beam index of a prefix that entered
                                  // in this generation's frame, keyed by prefix hash
 };
 
 // What a streaming (chunked) decode carries from one call to the next, per utterance: the
 // beam and its links as they stand after the last frame seen, plus the scalars the frame
 // loop keeps in registers.  The prefix trie lives behind the array of these records.
+template <int MB>
 struct StreamState {
     int32_t frames_done;  // frames decoded so far (= trie frame index of the next one)
     int32_t n_live;
     int32_t collapsed;
     int32_t pad;
     double bias, kmax, kmin;
-    BeamSlab slab;
-    int32_t par[kMaxBeam];
-    int32_t first_kid[kMaxBeam];
-    int32_t next_kid[kMaxBeam];
-    uint32_t kidmask[kMaxBeam];
+    BeamSlab<MB> slab;
+    int32_t par[MB];
+    int32_t first_kid[MB];
+    int32_t next_kid[MB];
+    uint32_t kidmask[MB];
 };
-static_assert(sizeof(StreamState) % 8 == 0, "records sit in an array: doubles stay aligned");
-static_assert(offsetof(Links, ht) == 4 * kMaxBeam * sizeof(int32_t),
+static_assert(sizeof(StreamState<kBeamSmall>) % 8 == 0 && sizeof(StreamState<kBeamLarge>) % 8 == 0,
+              "records sit in an array: doubles stay aligned");
+static_assert(offsetof(Links<kBeamSmall>, ht) == 4 * kBeamSmall * sizeof(int32_t) &&
+                  offsetof(Links<kBeamLarge>, ht) == 4 * kBeamLarge * sizeof(int32_t),
               "the four link arrays are the head of Links");
 
 struct BeamArgs {
@@ -108,7 +116,7 @@ struct BeamArgs {
     double lm_alpha, lm_beta;
     int32_t B, T, V, beam;
     int32_t lm_in_lds;  // 1: table staged into LDS
-    StreamState* stream;   // streaming decode: carried state (NULL for a one-shot decode)
+    void* stream;          // streaming decode: array of StreamState<MB> (NULL for a one-shot decode)
     int32_t t_total;       // streaming: frames the trie and the output rows are sized for
     int32_t out_stride;    // row length of out_tokens and of the traces
     double beam_window;  // SelectTopK's score window below the frame's best candidate; <= 0: off
@@ -320,9 +328,10 @@ typedef const __attribute__((address_space(3))) float* LdsFloatPtr;
 
 // Uniform per-frame values the candidate evaluation needs.  Only ever read through
 // constant field names, so it dissolves into registers after inlining.
+template <int MB>
 struct FrameCtx {
-    const BeamSlab* cur;
-    const Links* lk;
+    const BeamSlab<MB>* cur;
+    const Links<MB>* lk;
     const float* dense_lp;   // LDS, K > 6 only: log-prob by token, -inf if pruned
     const uint16_t* s_tok;   // LDS, K > 6 only: surviving tokens, ascending
     LdsFloatPtr lm_lds;      // LM table staged in LDS (kernel variant kLmLds)
@@ -373,14 +382,16 @@ __device__ __forceinline__ float pick_lp(int32_t tok, int32_t t0, int32_t t1, in
     return r;
 }
 
-__device__ __forceinline__ int32_t surv_tok(const FrameCtx& f, int k) {
+template <int MB>
+__device__ __forceinline__ int32_t surv_tok(const FrameCtx<MB>& f, int k) {
     if (f.big) return (int32_t)f.s_tok[k];
     const int32_t t0 = f.t0, t1 = f.t1, t2 = f.t2, t3 = f.t3, t4 = f.t4, t5 = f.t5;
     return pick_tok(k, t0, t1, t2, t3, t4, t5);
 }
 
 // log-prob of a token in this frame, -inf when it did not survive (or tok < 0)
-__device__ __forceinline__ double lp_of(const FrameCtx& f, int32_t tok) {
+template <int MB>
+__device__ __forceinline__ double lp_of(const FrameCtx<MB>& f, int32_t tok) {
     if (tok < 0) return -INFINITY;
     if (f.big) return (double)f.dense_lp[tok];
     const int32_t t0 = f.t0, t1 = f.t1, t2 = f.t2, t3 = f.t3, t4 = f.t4, t5 = f.t5;
@@ -392,8 +403,8 @@ __device__ __forceinline__ double lp_of(const FrameCtx& f, int32_t tok) {
 // LDS read and the global read would meet at a joint wait on both memory counters.
 enum : int { kLmNone = 0, kLmLds = 1, kLmGlobal = 2 };
 
-template <int LM>
-__device__ __forceinline__ double lm_term(const FrameCtx& f, int32_t prev, int32_t tok) {
+template <int LM, int MB>
+__device__ __forceinline__ double lm_term(const FrameCtx<MB>& f, int32_t prev, int32_t tok) {
     if (LM == kLmNone) return 0.0;
     const int32_t row = prev < 0 ? 0 : prev;
     const int64_t at = (int64_t)row * f.V + tok;
@@ -404,8 +415,8 @@ __device__ __forceinline__ double lm_term(const FrameCtx& f, int32_t prev, int32
 // Extension candidate e = i * Knb + k (entry i, non-blank survivor k): distance of its
 // score below the reference, or ~0 when it has no mass or coincides with a beam entry
 // (that entry's own update absorbs it).
-template <int LM>
-__device__ __forceinline__ uint64_t eval_ext(const FrameCtx& f, int e, int& src_entry,
+template <int LM, int MB>
+__device__ __forceinline__ uint64_t eval_ext(const FrameCtx<MB>& f, int e, int& src_entry,
                                              int32_t& tok) {
     const int i = f.Knb > 1 ? (int)__umulhi((uint32_t)e, f.div_magic) : e;
     const int k = e - i * f.Knb;
@@ -419,7 +430,7 @@ __device__ __forceinline__ uint64_t eval_ext(const FrameCtx& f, int e, int& src_
     const double pbi = f.collapsed ? pti : f.cur->pb[i];
     if ((km >> (s & 31)) & 1u) {  // maybe a child i+s is in the beam
         int guard = 0;
-        for (int kid = f.lk->first_kid[i]; kid >= 0 && guard < kMaxBeam;
+        for (int kid = f.lk->first_kid[i]; kid >= 0 && guard < MB;
              kid = f.lk->next_kid[kid], ++guard)
             if (f.cur->last[kid] == s) return kAllOnes;
     }
@@ -429,7 +440,8 @@ __device__ __forceinline__ uint64_t eval_ext(const FrameCtx& f, int e, int& src_
     return f.Rk - order_key(sc);
 }
 
-__device__ __forceinline__ uint64_t cand_hash(const FrameCtx& f, int src_entry, int32_t tok) {
+template <int MB>
+__device__ __forceinline__ uint64_t cand_hash(const FrameCtx<MB>& f, int src_entry, int32_t tok) {
     const uint64_t h = f.cur->h[src_entry];
     return tok < 0 ? h : child_hash(h, tok);
 }
@@ -440,7 +452,8 @@ __device__ __forceinline__ int window_bin(const Window& w, uint64_t x) {
 }
 
 // One candidate into the two-level histogram of the current window.
-__device__ __forceinline__ void hist_add(const FrameCtx& f, const Window& w, uint64_t D, int se,
+template <int MB>
+__device__ __forceinline__ void hist_add(const FrameCtx<MB>& f, const Window& w, uint64_t D, int se,
                                          int32_t tk, uint32_t* hfine, uint32_t* hcoarse) {
     uint64_t x = D;
     if (w.mode != 0) {
@@ -456,7 +469,8 @@ __device__ __forceinline__ void hist_add(const FrameCtx& f, const Window& w, uin
 // The same for the candidates beyond the register cache, of which a frame may have
 // thousands.  All that lie beyond the window share the last bin, and one LDS word cannot
 // take that many atomics quickly: those are counted in a register (`n_clamp`) instead.
-__device__ __forceinline__ void hist_add_many(const FrameCtx& f, const Window& w, uint64_t D,
+template <int MB>
+__device__ __forceinline__ void hist_add_many(const FrameCtx<MB>& f, const Window& w, uint64_t D,
                                               int se, int32_t tk, uint32_t* hfine,
                                               uint32_t* hcoarse, int& n_clamp) {
     uint64_t x = D;
@@ -475,7 +489,8 @@ __device__ __forceinline__ void hist_add_many(const FrameCtx& f, const Window& w
 }
 
 // One candidate into the boundary list if it falls into bucket `bstar`.
-__device__ __forceinline__ void boundary_add(const FrameCtx& f, const Window& w, int bstar,
+template <int MB>
+__device__ __forceinline__ void boundary_add(const FrameCtx<MB>& f, const Window& w, int bstar,
                                              uint64_t D, int se, int32_t tk, int32_t* count,
                                              uint64_t* bl_D, uint64_t* bl_h) {
     uint64_t x = D;
@@ -499,7 +514,8 @@ __device__ __forceinline__ void boundary_add(const FrameCtx& f, const Window& w,
 
 // Kept iff (D, hash) <= (selD, selH) lexicographically; the hash is computed only on
 // a distance tie.
-__device__ __forceinline__ bool is_selected(const FrameCtx& f, uint64_t selD, uint64_t selH,
+template <int MB>
+__device__ __forceinline__ bool is_selected(const FrameCtx<MB>& f, uint64_t selD, uint64_t selH,
                                             uint64_t D, int se, int32_t tk, uint64_t& hh,
                                             bool& have_h) {
     if (D < selD) return true;
@@ -509,7 +525,9 @@ __device__ __forceinline__ bool is_selected(const FrameCtx& f, uint64_t selD, ui
     return hh <= selH;
 }
 
-__device__ __forceinline__ void publish_hash(Links* lkn, uint64_t hh, int slot) {
+template <int MB>
+__device__ __forceinline__ void publish_hash(Links<MB>* lkn, uint64_t hh, int slot) {
+    constexpr int kHashSlots = 4 * MB;
     uint32_t hs = (uint32_t)hh & (kHashSlots - 1);
     for (int probe = 0; probe < kHashSlots; ++probe) {
         if (atomicCAS(&lkn->ht[hs], -1, slot) == -1) break;
@@ -518,11 +536,12 @@ __device__ __forceinline__ void publish_hash(Links* lkn, uint64_t hh, int slot) 
 }
 
 // Entry `se` keeps its prefix: copy it into `slot` of the next beam with its new masses.
-__device__ __forceinline__ void emit_stay(const FrameCtx& f, BeamSlab* nxt, Links* lkn,
+template <int MB>
+__device__ __forceinline__ void emit_stay(const FrameCtx<MB>& f, BeamSlab<MB>* nxt, Links<MB>* lkn,
                                           int32_t* newslot, int slot, int beam, int se, double pb,
                                           double pnb, double tot) {
     if (slot >= beam) return;  // only after a hash collision
-    const BeamSlab* cur = f.cur;
+    const BeamSlab<MB>* cur = f.cur;
     const uint64_t hh = cur->h[se];
     // where this entry went, and where its parent was (or -2: the parent was not in the
     // beam, so it can only be in the new one as a fresh extension)
@@ -542,12 +561,13 @@ __device__ __forceinline__ void emit_stay(const FrameCtx& f, BeamSlab* nxt, Link
 
 // Entry `se` extended by token `tk` becomes a new prefix in `slot`; its trie node id is
 // fixed by (frame, slot), so no counter is needed.
-__device__ __forceinline__ void emit_ext(const FrameCtx& f, BeamSlab* nxt, Links* lkn, int slot,
+template <int MB>
+__device__ __forceinline__ void emit_ext(const FrameCtx<MB>& f, BeamSlab<MB>* nxt, Links<MB>* lkn, int slot,
                                          int beam, int t, uint64_t D, int se, int32_t tk,
                                          uint64_t hh, bool have_h, TrieNode* trie,
                                          int64_t trie_stride) {
     if (slot >= beam) return;
-    const BeamSlab* cur = f.cur;
+    const BeamSlab<MB>* cur = f.cur;
     if (!have_h) hh = cand_hash(f, se, tk);
     const double sc = key_value(f.Rk - D);
     const int node = 1 + t * beam + slot;
@@ -572,11 +592,14 @@ __device__ __forceinline__ void emit_ext(const FrameCtx& f, BeamSlab* nxt, Links
     publish_hash(lkn, hh, slot);
 }
 
-template <int LM, int THREADS>
+template <int LM, int THREADS, int MB>
 __global__ __launch_bounds__(THREADS) void beam_kernel(BeamArgs a) {
     constexpr int kThreads = THREADS;
-    __shared__ BeamSlab slab[2];
-    __shared__ Links links[2];
+    constexpr int kMaxBeam = MB;
+    constexpr int kHashSlots = 4 * MB;
+    static_assert(THREADS >= MB, "one thread per beam entry");
+    __shared__ BeamSlab<MB> slab[2];
+    __shared__ Links<MB> links[2];
     __shared__ __align__(16) uint32_t hfine[kFine];
     __shared__ __align__(16) uint32_t hcoarse[kCoarse];
     __shared__ uint64_t bl_D[kExactCap], bl_h[kExactCap];
@@ -599,7 +622,8 @@ __global__ __launch_bounds__(THREADS) void beam_kernel(BeamArgs a) {
     float* lm_s = reinterpret_cast<float*>(dyn_lds + lm_lds_offset(V));
     constexpr bool has_lm = LM != kLmNone;
 
-    StreamState* const carried = a.stream ? a.stream + b : nullptr;  // uniform
+    StreamState<MB>* const carried =
+        a.stream ? static_cast<StreamState<MB>*>(a.stream) + b : nullptr;  // uniform
     const int32_t t_base = carried ? carried->frames_done : 0;
     int32_t len = a.lengths[b];
     len = len < 0 ? 0 : (len > a.T ? a.T : len);
@@ -647,12 +671,12 @@ __global__ __launch_bounds__(THREADS) void beam_kernel(BeamArgs a) {
         __syncthreads();  // the link arrays were just preset by other threads
         const uint32_t* src = reinterpret_cast<const uint32_t*>(&carried->slab);
         uint32_t* dst = reinterpret_cast<uint32_t*>(&slab[0]);
-        for (int i = tid; i < (int)(sizeof(BeamSlab) / 4); i += kThreads) dst[i] = src[i];
+        for (int i = tid; i < (int)(sizeof(BeamSlab<MB>) / 4); i += kThreads) dst[i] = src[i];
         const uint32_t* lsrc = reinterpret_cast<const uint32_t*>(carried->par);
         uint32_t* ldst = reinterpret_cast<uint32_t*>(&links[0]);
         for (int i = tid; i < 4 * kMaxBeam; i += kThreads) ldst[i] = lsrc[i];
     } else if (tid == 0) {
-        BeamSlab& s0 = slab[0];
+        BeamSlab<MB>& s0 = slab[0];
         s0.h[0] = kGolden;
         s0.hp[0] = 0;
         s0.pb[0] = 0.0;
@@ -667,7 +691,7 @@ __global__ __launch_bounds__(THREADS) void beam_kernel(BeamArgs a) {
     const double lm_ub = has_lm ? fmax(0.0, (double)a.lm_bound[0]) : 0.0;
     __syncthreads();
 
-    FrameCtx fc;
+    FrameCtx<MB> fc;
     fc.dense_lp = dense_lp;
     fc.s_tok = s_tok;
     fc.lm_lds = (LdsFloatPtr)lm_s;
@@ -750,10 +774,10 @@ __global__ __launch_bounds__(THREADS) void beam_kernel(BeamArgs a) {
         const FrameHdr hd = ring[t % kChunk];  // all 64 bytes in one round trip
         const int K = hd.count;
 
-        BeamSlab* const cur = &slab[gen];
-        BeamSlab* const nxt = &slab[gen ^ 1];
-        Links* const lk = &links[gen];
-        Links* const lkn = &links[gen ^ 1];
+        BeamSlab<MB>* const cur = &slab[gen];
+        BeamSlab<MB>* const nxt = &slab[gen ^ 1];
+        Links<MB>* const lk = &links[gen];
+        Links<MB>* const lkn = &links[gen ^ 1];
 
         // ---- survivors: registers for K <= 6, LDS staging beyond ------------------------
         const bool big = K > kRegK;
@@ -1160,7 +1184,7 @@ __global__ __launch_bounds__(THREADS) void beam_kernel(BeamArgs a) {
     __syncthreads();
 
     // ---- best prefix (paper: GetHighestScorePrefix) ----------------------------------
-    BeamSlab& fin = slab[gen];
+    BeamSlab<MB>& fin = slab[gen];
     int32_t* wp_node = reinterpret_cast<int32_t*>(hfine);  // the histogram is idle now
     int32_t* wp_depth = wp_node + kWaypoints;
     static_assert(2 * kWaypoints <= kFine, "way-points alias the histogram");
@@ -1281,7 +1305,7 @@ __global__ __launch_bounds__(THREADS) void beam_kernel(BeamArgs a) {
     if (carried) {
         const uint32_t* src = reinterpret_cast<const uint32_t*>(&slab[gen]);
         uint32_t* dst = reinterpret_cast<uint32_t*>(&carried->slab);
-        for (int i = tid; i < (int)(sizeof(BeamSlab) / 4); i += kThreads) dst[i] = src[i];
+        for (int i = tid; i < (int)(sizeof(BeamSlab<MB>) / 4); i += kThreads) dst[i] = src[i];
         const uint32_t* lsrc = reinterpret_cast<const uint32_t*>(&links[gen]);
         uint32_t* ldst = reinterpret_cast<uint32_t*>(carried->par);
         for (int i = tid; i < 4 * kMaxBeam; i += kThreads) ldst[i] = lsrc[i];
@@ -1297,12 +1321,14 @@ __global__ __launch_bounds__(THREADS) void beam_kernel(BeamArgs a) {
 }
 
 // A fresh stream: the empty prefix with score 0, no links, no frames seen.
-__global__ __launch_bounds__(kThreadsSmall) void stream_begin_kernel(StreamState* st, int32_t B) {
+template <int MB>
+__global__ __launch_bounds__(kThreadsSmall) void stream_begin_kernel(StreamState<MB>* st, int32_t B) {
     constexpr int kThreads = kThreadsSmall;
+    constexpr int kMaxBeam = MB;
     for (int32_t b = blockIdx.x; b < B; b += gridDim.x) {
-        StreamState* s = st + b;
+        StreamState<MB>* s = st + b;
         uint32_t* words = reinterpret_cast<uint32_t*>(s);
-        for (int i = threadIdx.x; i < (int)(sizeof(StreamState) / 4); i += kThreads) words[i] = 0u;
+        for (int i = threadIdx.x; i < (int)(sizeof(StreamState<MB>) / 4); i += kThreads) words[i] = 0u;
         __syncthreads();
         for (int i = threadIdx.x; i < kMaxBeam; i += kThreads) {
             s->par[i] = -1;
@@ -1340,11 +1366,18 @@ hipError_t launch_log_add(const double* a, const double* b, double* out, int64_t
     return hipGetLastError();
 }
 
-size_t stream_record_bytes() { return sizeof(StreamState); }
+size_t stream_record_bytes(int32_t beam) {
+    return beam <= kBeamSmall ? sizeof(StreamState<kBeamSmall>) : sizeof(StreamState<kBeamLarge>);
+}
 
-hipError_t launch_stream_begin(void* records, int32_t B, hipStream_t stream) {
-    hipLaunchKernelGGL(stream_begin_kernel, dim3((unsigned)(B < 1024 ? B : 1024)), dim3(kThreadsSmall),
-                       0, stream, static_cast<StreamState*>(records), B);
+hipError_t launch_stream_begin(void* records, int32_t B, int32_t beam, hipStream_t stream) {
+    const dim3 grid((unsigned)(B < 1024 ? B : 1024));
+    if (beam <= kBeamSmall)
+        hipLaunchKernelGGL(stream_begin_kernel<kBeamSmall>, grid, dim3(kThreadsSmall), 0, stream,
+                           static_cast<StreamState<kBeamSmall>*>(records), B);
+    else
+        hipLaunchKernelGGL(stream_begin_kernel<kBeamLarge>, grid, dim3(kThreadsSmall), 0, stream,
+                           static_cast<StreamState<kBeamLarge>*>(records), B);
     return hipGetLastError();
 }
 
@@ -1358,7 +1391,7 @@ hipError_t launch_beam(const int32_t* lengths, int32_t B, int32_t T, int32_t V,
     a.rec = ws.rec;
     a.trie = carried ? carried->trie : ws.trie;
     a.trie_stride = carried ? carried->trie_stride : ws.trie_stride;
-    a.stream = carried ? static_cast<StreamState*>(carried->records) : nullptr;
+    a.stream = carried ? carried->records : nullptr;
     a.t_total = carried ? carried->t_total : T;
     a.out_stride = carried ? carried->t_total : T;
     a.lm_table = p.lm_table;
@@ -1389,15 +1422,21 @@ hipError_t launch_beam(const int32_t* lengths, int32_t B, int32_t T, int32_t V,
     // vocabulary leaves hundreds to thousands of candidates per frame, which eight wavefronts
     // (two per SIMD) evaluate twice as fast (measured: V = 1024 27% faster per decode with 512
     // threads, V = 32 at r = 0.01 6% slower).
+    // Beam capacity: up to 128 entries the beam state takes 30 KB of LDS and five workgroups
+    // share a CU; beyond, the 512-entry build (100 KB, one thread per entry) is used.
     const bool wide = V > 64;
+    const bool large_beam = p.beam > kBeamSmall;
 #define FLTOP_LAUNCH_BEAM(LM_)                                                               \
     do {                                                                                     \
-        if (wide)                                                                            \
-            hipLaunchKernelGGL((beam_kernel<LM_, kThreadsLarge>), dim3((unsigned)B),         \
-                               dim3(kThreadsLarge), dyn, stream, a);                         \
+        if (large_beam)                                                                      \
+            hipLaunchKernelGGL((beam_kernel<LM_, kThreadsLarge, kBeamLarge>),                \
+                               dim3((unsigned)B), dim3(kThreadsLarge), dyn, stream, a);      \
+        else if (wide)                                                                       \
+            hipLaunchKernelGGL((beam_kernel<LM_, kThreadsLarge, kBeamSmall>),                \
+                               dim3((unsigned)B), dim3(kThreadsLarge), dyn, stream, a);      \
         else                                                                                 \
-            hipLaunchKernelGGL((beam_kernel<LM_, kThreadsSmall>), dim3((unsigned)B),         \
-                               dim3(kThreadsSmall), dyn, stream, a);                         \
+            hipLaunchKernelGGL((beam_kernel<LM_, kThreadsSmall, kBeamSmall>),                \
+                               dim3((unsigned)B), dim3(kThreadsSmall), dyn, stream, a);      \
     } while (0)
     if (p.lm_table == nullptr)
         FLTOP_LAUNCH_BEAM(kLmNone);

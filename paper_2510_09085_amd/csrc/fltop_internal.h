@@ -92,13 +92,13 @@ struct StreamSpace {
     size_t bytes;
 };
 
-size_t stream_record_bytes();
+size_t stream_record_bytes(int32_t beam);
 
 inline StreamSpace carve_stream(void* base, int32_t B, int32_t t_total, int32_t beam) {
     StreamSpace s;
     s.t_total = t_total;
     s.trie_stride = (int64_t)t_total * beam + 1;
-    const size_t off_trie = align_up((size_t)B * stream_record_bytes(), 256);
+    const size_t off_trie = align_up((size_t)B * stream_record_bytes(beam), 256);
     s.bytes = align_up(off_trie + (size_t)B * (size_t)s.trie_stride * sizeof(TrieNode), 256);
     char* p = static_cast<char*>(base);
     s.records = p;
@@ -106,7 +106,7 @@ inline StreamSpace carve_stream(void* base, int32_t B, int32_t t_total, int32_t 
     return s;
 }
 
-hipError_t launch_stream_begin(void* records, int32_t B, hipStream_t stream);
+hipError_t launch_stream_begin(void* records, int32_t B, int32_t beam, hipStream_t stream);
 hipError_t launch_log_add(const double* a, const double* b, double* out, int64_t n,
                           hipStream_t stream);
 

@@ -316,19 +316,57 @@ def test_workload_cfg5(dev, oracle_lib, r):
 # --------------------------------------------------------------------------- size limits
 def test_largest_vocabulary_and_beam(dev, oracle_lib):
     """V = FLTOP_MAX_VOCAB, beam = FLTOP_MAX_BEAM: every lane chunk of the prune stage and every
-    beam slot of the search stage is in use."""
+    beam slot of the search stage is in use (and the LDS budget is at its largest)."""
     V, beam = binding.MAX_VOCAB, binding.MAX_BEAM
-    lp = synth.random_emissions(4096, 2, 12, V, flat=3.0)
-    ln = np.array([12, 7], dtype=np.int32)
+    lp = synth.random_emissions(4096, 2, 5, V, flat=3.0)
+    ln = np.array([5, 3], dtype=np.int32)
     for r in (0.0, 0.002):
         want = oracle_lib.decode(lp, ln, beam, r, n_threads=2)
         got = gpu_decode(dev, lp, ln, beam, r)
         assert_parity(got, want[0], want[1], want[2], f"V{V} beam{beam} r{r}")
+    lm = synth.make_bigram_lm(64, seed=3)  # 16 KB table in LDS next to the 512-entry beam
+    lp2 = synth.random_emissions(4097, 2, 40, 64, flat=1.5)
+    ln2 = np.array([40, 17], dtype=np.int32)
+    want = oracle_lib.decode(lp2, ln2, beam, 0.0, lm_table=lm, lm_weight=0.5, insertion_bonus=1.0,
+                             n_threads=2)
+    got = gpu_decode(dev, lp2, ln2, beam, 0.0, lm, 0.5, 1.0)
+    assert_parity(got, want[0], want[1], want[2], "V64 beam max with LM in LDS")
     lp_d = torch.from_numpy(lp).to(dev)
     ln_d = torch.from_numpy(ln).to(dev)
     ws = binding.prune(lp_d, ln_d, beam, 0.0)
-    counts = binding.unpack_survivors(ws, ln_d, 2, 12, V, beam)[0].cpu().numpy()
-    assert (counts[:12] == V).all() and (counts[12:19] == V).all() and (counts[19:] == 0).all()
+    counts = binding.unpack_survivors(ws, ln_d, 2, 5, V, beam)[0].cpu().numpy()
+    assert (counts[:5] == V).all() and (counts[5:8] == V).all() and (counts[8:] == 0).all()
+
+
+@pytest.mark.parametrize("beam", [129, 200, 300, 512])
+def test_beams_above_the_small_capacity(dev, oracle_lib, beam):
+    """Beams above 128 entries run the 512-entry build of the search stage."""
+    for seed, (B, T, V, r, window) in enumerate([(2, 80, 32, 0.0, 0.0), (3, 120, 32, 0.01, 8.0),
+                                                 (2, 60, 64, 0.0, 25.0)]):
+        lp = synth.random_emissions(500 + beam + seed, B, T, V, flat=1.2)
+        ln = np.array([T] * (B - 1) + [T // 2], dtype=np.int32)
+        want = oracle_lib.decode(lp, ln, beam, r, beam_threshold=window, n_threads=4)
+        lp_d, ln_d = torch.from_numpy(lp).to(dev), torch.from_numpy(ln).to(dev)
+        out = binding.decode(lp_d, ln_d, beam, r, beam_threshold=window, want_stats=True,
+                             want_nbest=(seed == 0))
+        torch.cuda.synchronize()
+        lens = out["lengths"].cpu().numpy()
+        toks = out["tokens"].cpu().numpy()
+        got = {"tokens": [toks[b, :lens[b]].tolist() for b in range(B)],
+               "scores": out["scores"].cpu().numpy(), "stats": binding.stats_dict(out["stats"])}
+        assert_parity(got, want[0], want[1], want[2], f"beam {beam} case {seed}")
+        if seed == 0:  # the whole final beam of the first utterance, in rank order
+            ref = oracle_lib.decode_beam(lp[0], beam, r, max_entries=beam)
+            cnt = int(out["nbest_count"][0])
+            assert cnt == len(ref)
+            nt = out["nbest_tokens"][0].cpu().numpy()
+            nl = out["nbest_lengths"][0].cpu().numpy()
+            pb = out["nbest_pb"][0].cpu().numpy()
+            pnb = out["nbest_pnb"][0].cpu().numpy()
+            for e in range(cnt):
+                assert tuple(nt[e, :nl[e]].tolist()) == ref[e][0], f"entry {e}"
+                for g, w in ((pb[e], ref[e][1]), (pnb[e], ref[e][2])):
+                    assert (g == w) or abs(g - w) <= 1e-9
 
 
 def test_more_utterances_than_one_grid_dimension_holds(dev, oracle_lib):

@@ -132,9 +132,17 @@ def test_unpruned_chunks_and_restart(dev, oracle_lib):
             assert toks[b, :lens[b]].tolist() == want[0][b], f"restart {rep}"
 
 
+def test_chunked_decode_with_a_large_beam(dev, oracle_lib):
+    lp = synth.random_emissions(92, 2, 90, 32, flat=1.5)
+    ln = np.array([90, 61], dtype=np.int32)
+    want = oracle_lib.decode(lp, ln, 300, 0.001, traces=True, n_threads=2)
+    got = feed_in_chunks(dev, lp, ln, 40, 300, 0.001)
+    check_final(got, want, ln, "beam 300 in chunks of 40")
+
+
 def test_stream_argument_errors(dev):
     assert binding.load().fltop_ctc_stream_state_bytes(0, 10, 4) == 0
-    assert binding.load().fltop_ctc_stream_state_bytes(2, 10, 500) == 0
+    assert binding.load().fltop_ctc_stream_state_bytes(2, 10, binding.MAX_BEAM + 1) == 0
     st = binding.Stream(1, 8, 4, 8, 4, 0.1, dev)
     with pytest.raises(ValueError):
         st.feed(torch.zeros((1, 5, 8), dtype=torch.float32, device=dev),

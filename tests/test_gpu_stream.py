@@ -153,3 +153,50 @@ def test_stream_argument_errors(dev):
                 torch.full((1,), 4, dtype=torch.int32, device=dev))
     torch.cuda.synchronize()
     assert int(st.stats.cpu()[0]) >= 8  # frames counted: 4 + 4 (+ 0 for the chunk beyond the end)
+
+
+def test_decode_can_be_captured_in_a_graph_and_replayed(dev, oracle_lib):
+    """The entry points only enqueue kernels on the given stream (no allocation, no memset, no
+    host synchronisation), so a serving loop can capture a decode once and replay it: every
+    replay, with fresh emissions copied into the captured input buffer and the program's own
+    eager work in between, must give what an eager call gives."""
+    w = synth.WORKLOADS["cfg2_batch64"]
+    lp_all, ln_all = synth.make_emissions(w, utterances=range(12))
+    B = 4
+    static_lp = torch.empty((B, w.T, w.V), dtype=torch.float32, device=dev)
+    static_ln = torch.empty(B, dtype=torch.int32, device=dev)
+    ws = binding.alloc_workspace(B, w.T, w.V, w.beam, dev)
+    tok = torch.full((B, w.T), -1, dtype=torch.int32, device=dev)
+    olen = torch.zeros(B, dtype=torch.int32, device=dev)
+    sc = torch.zeros(B, dtype=torch.float32, device=dev)
+    p = binding.FltopParams()
+    p.beam = w.beam
+    p.rel_threshold = 0.01
+    static_lp.copy_(torch.from_numpy(lp_all[:B]))
+    static_ln.copy_(torch.from_numpy(ln_all[:B]))
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):  # warm-up outside the capture
+        assert binding.decode_raw(static_lp, static_ln, p, ws, ws.numel(), tok, olen, sc, None) == 0
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        rc = binding.decode_raw(static_lp, static_ln, p, ws, ws.numel(), tok, olen, sc, None)
+    assert rc == 0
+    for rep in range(3):
+        sl = slice(rep * B, rep * B + B)
+        static_lp.copy_(torch.from_numpy(lp_all[sl]))
+        static_ln.copy_(torch.from_numpy(ln_all[sl]))
+        tok.fill_(-1)
+        graph.replay()
+        torch.cuda.synchronize()
+        eager = binding.decode(static_lp, static_ln, w.beam, 0.01)  # eager work between replays
+        torch.cuda.synchronize()
+        want = oracle_lib.decode(lp_all[sl], ln_all[sl], w.beam, 0.01, n_threads=4)
+        lens = olen.cpu().numpy()
+        toks = tok.cpu().numpy()
+        for b in range(B):
+            assert toks[b, :lens[b]].tolist() == want[0][b], f"replay {rep}, utterance {b}"
+        np.testing.assert_array_equal(sc.cpu().numpy(), eager["scores"].cpu().numpy())
+        np.testing.assert_array_equal(lens, eager["lengths"].cpu().numpy())

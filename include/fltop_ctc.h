@@ -35,8 +35,9 @@
  * row-major and densely packed.  The caller owns every buffer; the library
  * allocates nothing, keeps no state between calls and may be called
  * concurrently on different streams with different workspaces.  All work is
- * enqueued on `stream`; no entry point synchronises with the host, so outputs
- * are valid once the stream has reached that point.  Every function that
+ * enqueued on `stream` as kernel launches only (so a call may be captured in a HIP
+ * graph); no entry point synchronises with the host, so outputs are valid once the
+ * stream has reached that point.  Every function that
  * returns int returns FLTOP_OK (0) or a negative FLTOP_ERR_* value; on an
  * error nothing has been enqueued.  There is no CPU fallback.
  */

@@ -688,7 +688,14 @@ __global__ __launch_bounds__(THREADS) void beam_kernel(BeamArgs a) {
         s0.xanc[0] = 0;
     }
     TrieNode* trie = a.trie + (int64_t)b * trie_stride;
-    const double lm_ub = has_lm ? fmax(0.0, (double)a.lm_bound[0]) : 0.0;
+    double lm_ub = 0.0;  // upper bound of any LM term (never below 0)
+    if (has_lm) {
+        static_assert(kLmBoundParts == kWave, "one partial maximum per lane");
+        float part = a.lm_bound[lane];
+#pragma unroll
+        for (int o = kWave / 2; o > 0; o >>= 1) part = fmaxf(part, __shfl_xor(part, o, kWave));
+        lm_ub = fmax(0.0, (double)part);
+    }
     __syncthreads();
 
     FrameCtx<MB> fc;

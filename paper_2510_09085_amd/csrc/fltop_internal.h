@@ -22,6 +22,8 @@ struct alignas(8) Survivor {
 constexpr int kInlineSurvivors = 6;
 
 // Per-frame header written by the prune stage (one 64-byte line).
+constexpr int kLmBoundParts = 64;  // workgroups of the LM bound kernel = lanes that read them
+
 struct alignas(64) FrameHdr {
     int32_t count;       // |S_t| (0 for frames at or beyond the utterance length)
     int32_t has_blank;   // 1 if token 0 survived (it is survivor 0 then), else 0
@@ -57,7 +59,7 @@ struct Workspace {
     FrameHdr* hdr;      // [B*T]
     Survivor* rec;      // [B*T][V]: survivors of rank >= 6 (slot = rank)
     TrieNode* trie;     // [B][trie_stride]
-    float* lm_bound;    // [1] upper bound of lm_weight*table+bonus (or 0)
+    float* lm_bound;    // [kLmBoundParts] partial maxima of lm_weight*table+bonus
     int64_t trie_stride;
     size_t bytes;
 };

@@ -361,19 +361,23 @@ __global__ __launch_bounds__(kThreads) void unpack_kernel(
     }
 }
 
-// max over the table of lm_weight * table + bonus: bounds every LM term from above.
+// max over the table of lm_weight * table + bonus: bounds every LM term from above.  One
+// partial maximum per workgroup (kLmBoundParts of them; the search stage takes the max of
+// those), so that a 4 MB table is read by 64 workgroups and not by one.
 __global__ __launch_bounds__(kThreads) void lm_bound_kernel(const float* __restrict__ table,
                                                             int64_t n, float w, float bonus,
                                                             float* __restrict__ out) {
     __shared__ float s_part[kWaves];
     float m = -INFINITY;
-    for (int64_t i = threadIdx.x; i < n; i += kThreads) m = fmaxf(m, fmaf(w, table[i], bonus));
+    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n;
+         i += (int64_t)gridDim.x * kThreads)
+        m = fmaxf(m, fmaf(w, table[i], bonus));
     m = group_max<kWave>(m);
     if ((threadIdx.x & (kWave - 1)) == 0) s_part[threadIdx.x / kWave] = m;
     __syncthreads();
     if (threadIdx.x == 0) {
         for (int i = 1; i < kWaves; ++i) m = fmaxf(m, s_part[i]);
-        out[0] = m;
+        out[blockIdx.x] = m;
     }
 }
 
@@ -444,7 +448,7 @@ hipError_t launch_unpack(const Workspace& ws, const int32_t* lengths, int32_t B,
 
 hipError_t launch_lm_bound(const float* lm_table, int32_t V, float lm_weight, float bonus,
                            float* out, hipStream_t stream) {
-    hipLaunchKernelGGL(lm_bound_kernel, dim3(1), dim3(kThreads), 0, stream, lm_table,
+    hipLaunchKernelGGL(lm_bound_kernel, dim3(kLmBoundParts), dim3(kThreads), 0, stream, lm_table,
                        (int64_t)V * V, lm_weight, bonus, out);
     return hipGetLastError();
 }

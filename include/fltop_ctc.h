@@ -100,7 +100,7 @@ typedef struct fltop_stats {
     uint64_t sum_survivors;     /* sum over frames of |S_t|                                    */
     uint64_t sum_candidates;    /* sum over frames of distinct live candidate prefixes         */
     uint64_t peak_candidates;   /* max over frames (and utterances) of the same                */
-    uint64_t sum_beam;          /* sum over frames of entries kept by the top-`beam` cut       */
+    uint64_t sum_beam;          /* sum over frames of entries kept by SelectTopK               */
     uint64_t select_passes;     /* histogram passes spent in the top-`beam` selection          */
     uint64_t exact_rankings;    /* selections that needed the exact (score, hash) ranking      */
     uint64_t overflow_drops;    /* entries dropped because a hash collision overfilled a beam  */

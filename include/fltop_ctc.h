@@ -208,7 +208,8 @@ int fltop_ctc_token_ranks(const float* logprobs, int32_t B, int32_t T, int32_t V
                           const int32_t* token_counts, int32_t* out_ranks,
                           uint64_t* rank_count, double* rank_lp_sum, void* hip_stream);
 
-/* The two-operand log-sum-exp the search stage merges masses with, LSE(a,b) = max + log1p(
+/* The two-operand log-sum-exp with which the search stage merges the masses of equal
+ * prefixes (Algorithm 1's set insert B'.add) and forms a prefix's score, LSE(a,b) = max + log1p(
  * exp(min - max)) in fp64 with -inf as the neutral element, applied element-wise to dev
  * arrays of n values: exposed so that its rounding can be checked against a reference
  * (it is written out for the narrow argument ranges that occur, not taken from the math

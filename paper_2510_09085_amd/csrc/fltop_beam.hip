@@ -358,17 +358,6 @@ struct Window {
 
 // The register-resident survivors travel by value (twelve scalars): selecting among
 // fields read through a pointer would be turned into an indexed load, i.e. scratch.
-__device__ __forceinline__ int32_t pick_tok(int k, int32_t t0, int32_t t1, int32_t t2, int32_t t3,
-                                            int32_t t4, int32_t t5) {
-    int32_t r = t0;
-    r = (k == 1) ? t1 : r;
-    r = (k == 2) ? t2 : r;
-    r = (k == 3) ? t3 : r;
-    r = (k == 4) ? t4 : r;
-    r = (k == 5) ? t5 : r;
-    return r;
-}
-
 __device__ __forceinline__ float pick_lp(int32_t tok, int32_t t0, int32_t t1, int32_t t2,
                                          int32_t t3, int32_t t4, int32_t t5, float l0, float l1,
                                          float l2, float l3, float l4, float l5) {
@@ -382,11 +371,30 @@ __device__ __forceinline__ float pick_lp(int32_t tok, int32_t t0, int32_t t1, in
     return r;
 }
 
+// (token, log-prob) of survivor k in one pass: the index compares serve both selections
 template <int MB>
-__device__ __forceinline__ int32_t surv_tok(const FrameCtx<MB>& f, int k) {
-    if (f.big) return (int32_t)f.s_tok[k];
+__device__ __forceinline__ int32_t surv_tok_lp(const FrameCtx<MB>& f, int k, double& lp) {
+    if (f.big) {
+        const int32_t s = (int32_t)f.s_tok[k];
+        lp = (double)f.dense_lp[s];
+        return s;
+    }
     const int32_t t0 = f.t0, t1 = f.t1, t2 = f.t2, t3 = f.t3, t4 = f.t4, t5 = f.t5;
-    return pick_tok(k, t0, t1, t2, t3, t4, t5);
+    const float l0 = f.l0, l1 = f.l1, l2 = f.l2, l3 = f.l3, l4 = f.l4, l5 = f.l5;
+    int32_t r = t0;
+    float l = l0;
+    r = (k == 1) ? t1 : r;
+    l = (k == 1) ? l1 : l;
+    r = (k == 2) ? t2 : r;
+    l = (k == 2) ? l2 : l;
+    r = (k == 3) ? t3 : r;
+    l = (k == 3) ? l3 : l;
+    r = (k == 4) ? t4 : r;
+    l = (k == 4) ? l4 : l;
+    r = (k == 5) ? t5 : r;
+    l = (k == 5) ? l5 : l;
+    lp = (double)l;
+    return r;
 }
 
 // log-prob of a token in this frame, -inf when it did not survive (or tok < 0)
@@ -420,7 +428,8 @@ __device__ __forceinline__ uint64_t eval_ext(const FrameCtx<MB>& f, int e, int& 
                                              int32_t& tok) {
     const int i = f.Knb > 1 ? (int)__umulhi((uint32_t)e, f.div_magic) : e;
     const int k = e - i * f.Knb;
-    const int32_t s = surv_tok(f, f.nb0 + k);
+    double lps;
+    const int32_t s = surv_tok_lp(f, f.nb0 + k, lps);
     src_entry = i;
     tok = s;
     // the four reads go out together; the children list is walked only on a mask hit
@@ -435,7 +444,7 @@ __device__ __forceinline__ uint64_t eval_ext(const FrameCtx<MB>& f, int e, int& 
             if (f.cur->last[kid] == s) return kAllOnes;
     }
     const double src = (s == li) ? pbi : pti;
-    const double sc = src + lp_of(f, s) + lm_term<LM>(f, li, s);
+    const double sc = src + lps + lm_term<LM>(f, li, s);
     if (!(sc > -INFINITY)) return kAllOnes;
     return f.Rk - order_key(sc);
 }

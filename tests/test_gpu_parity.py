@@ -386,6 +386,26 @@ def test_more_utterances_than_one_grid_dimension_holds(dev, oracle_lib):
     assert got["stats"]["frames"] == int(ln.sum())
 
 
+@pytest.mark.parametrize("case", ["v32", "v32_lm", "v100_lm"])
+def test_batches_larger_than_the_chip_holds_at_once(dev, oracle_lib, case):
+    """More utterances than two workgroups per compute unit (one, for the 512-thread
+    build): the launcher then takes the build with the halved register budget."""
+    B, T, V, beam, r, lm_on = {"v32": (530, 36, 32, 32, 0.0, False),
+                               "v32_lm": (600, 40, 32, 16, 1e-3, True),
+                               "v100_lm": (300, 30, 100, 20, 1e-3, True)}[case]
+    assert B > (256 if V > 64 else 512)
+    lp = synth.random_emissions(4242 + V + B, B, T, V, flat=1.5)
+    rng = np.random.default_rng(B)
+    ln = rng.integers(0, T + 1, size=B).astype(np.int32)
+    ln[:4] = T
+    lm = synth.make_bigram_lm(V, seed=31) if lm_on else None
+    alpha, beta = (0.6, 0.4) if lm_on else (0.0, 0.0)
+    want = oracle_lib.decode(lp, ln, beam, r, lm_table=lm, lm_weight=alpha,
+                             insertion_bonus=beta, n_threads=8)
+    got = gpu_decode(dev, lp, ln, beam, r, lm=lm, alpha=alpha, beta=beta)
+    assert_parity(got, want[0], want[1], want[2], case)
+
+
 def test_all_utterances_empty(dev, oracle_lib):
     lp = np.full((3, 5, 8), np.nan, dtype=np.float32)
     ln = np.zeros(3, dtype=np.int32)

@@ -140,6 +140,17 @@ def test_chunked_decode_with_a_large_beam(dev, oracle_lib):
     check_final(got, want, ln, "beam 300 in chunks of 40")
 
 
+def test_chunked_decode_of_a_batch_larger_than_the_chip_holds(dev, oracle_lib):
+    """Above two workgroups per compute unit the halved-register build of the search kernel
+    runs; its carried state must round-trip like the other build's."""
+    B, T, V, beam = 520, 48, 32, 24
+    lp = synth.random_emissions(93, B, T, V, flat=1.5)
+    ln = np.random.default_rng(93).integers(0, T + 1, size=B).astype(np.int32)
+    want = oracle_lib.decode(lp, ln, beam, 1e-3, traces=True, n_threads=8)
+    got = feed_in_chunks(dev, lp, ln, 20, beam, 1e-3)
+    check_final(got, want, ln, "520 streams in chunks of 20")
+
+
 def test_stream_argument_errors(dev):
     assert binding.load().fltop_ctc_stream_state_bytes(0, 10, 4) == 0
     assert binding.load().fltop_ctc_stream_state_bytes(2, 10, binding.MAX_BEAM + 1) == 0

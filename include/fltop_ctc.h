@@ -33,7 +33,7 @@
  *
  * Conventions: "dev" = device (HBM) pointer, "host" = host pointer.  Arrays are
  * row-major and densely packed.  The caller owns every buffer; the library
- * allocates nothing, keeps no state between calls and may be called
+ * allocates nothing, keeps no decoding state between calls and may be called
  * concurrently on different streams with different workspaces.  All work is
  * enqueued on `stream` as kernel launches only (so a call may be captured in a HIP
  * graph); no entry point synchronises with the host, so outputs are valid once the

@@ -45,6 +45,17 @@ def build(sanitize: bool = False) -> str:
     return out
 
 
+def build_sanitize_driver(out: str) -> str:
+    """Compile sanitize_driver.cpp + the oracle into one executable under ASan and UBSan
+    (runtime linked statically, so it runs whatever else the loader preloads)."""
+    cmd = ["g++", "-O1", "-g", "-std=c++17", "-pthread", "-Wall", "-Wextra", "-ffp-contract=off",
+           "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined", "-static-libasan",
+           "-fno-omit-frame-pointer", os.path.join(_HERE, "sanitize_driver.cpp"),
+           os.path.join(_HERE, "fltop_oracle.cpp"), "-o", out]
+    subprocess.run(cmd, check=True)
+    return out
+
+
 _lib = None
 
 

@@ -406,6 +406,44 @@ def test_batches_larger_than_the_chip_holds_at_once(dev, oracle_lib, case):
     assert_parity(got, want[0], want[1], want[2], case)
 
 
+def test_same_input_twice_gives_identical_bytes(dev):
+    """Every log-sum-exp has two symmetric operands and ties are ordered by hash, so thread
+    timing cannot show: two decodes of the same input agree bit for bit, final beam included."""
+    w = synth.WORKLOADS["cfg5_bigram_lm"]
+    lp, ln = synth.make_emissions(w, utterances=range(24))
+    lm = torch.from_numpy(synth.make_bigram_lm(w.V)).to(dev)
+    lp_d, ln_d = torch.from_numpy(lp).to(dev), torch.from_numpy(ln).to(dev)
+    runs = []
+    for _ in range(2):
+        out = binding.decode(lp_d, ln_d, w.beam, 0.0, lm_table=lm, lm_weight=w.lm_weight,
+                             insertion_bonus=w.insertion_bonus, want_stats=True, want_nbest=True,
+                             want_traces=True)
+        torch.cuda.synchronize()
+        lens = out["lengths"].cpu().numpy()
+        cnt = out["nbest_count"].cpu().numpy()
+        nl = out["nbest_lengths"].cpu().numpy()
+        nt = out["nbest_tokens"].cpu().numpy()
+        runs.append({
+            "lengths": lens.tobytes(),
+            "tokens": b"".join(out["tokens"][b, :lens[b]].cpu().numpy().tobytes()
+                               for b in range(len(lens))),
+            "scores": out["scores"].cpu().numpy().tobytes(),
+            "nbest_count": cnt.tobytes(),
+            "nbest_lengths": b"".join(nl[b, :cnt[b]].tobytes() for b in range(len(lens))),
+            "nbest_tokens": b"".join(nt[b, e, :nl[b, e]].tobytes()
+                                     for b in range(len(lens)) for e in range(cnt[b])),
+            "nbest_pb": b"".join(out["nbest_pb"][b, :cnt[b]].cpu().numpy().tobytes()
+                                 for b in range(len(lens))),
+            "nbest_pnb": b"".join(out["nbest_pnb"][b, :cnt[b]].cpu().numpy().tobytes()
+                                  for b in range(len(lens))),
+            "frame_beam": out["frame_beam"].cpu().numpy().tobytes(),
+            "stats": tuple(sorted((k, v) for k, v in binding.stats_dict(out["stats"]).items()
+                                  if not k.startswith("clk"))),
+        })
+    for key in runs[0]:
+        assert runs[0][key] == runs[1][key], key
+
+
 def test_all_utterances_empty(dev, oracle_lib):
     lp = np.full((3, 5, 8), np.nan, dtype=np.float32)
     ln = np.zeros(3, dtype=np.int32)

@@ -42,10 +42,12 @@ namespace {
 
 constexpr int kThreadsSmall = 256;  // workgroup size for small vocabularies
 constexpr int kThreadsLarge = 512;  // and for large ones (see launch_beam)
+constexpr int kThreadsDense = 128;  // small frames, batches larger than the chip holds at once
 constexpr int kWave = 64;
 // The beam lives in LDS, so its capacity is a compile-time size: kernels are built for a
 // small one (which keeps several workgroups per CU for large batches) and for the largest.
 constexpr int kBeamSmall = 128;
+constexpr int kBeamTiny = 64;  // one-shot decodes of dense batches (17 KB of LDS)
 constexpr int kBeamLarge = FLTOP_MAX_BEAM;
 static_assert(kBeamLarge == 512, "the LDS budget below is worked out for 512 entries");
 constexpr int kFine = 1024;  // histogram bins
@@ -602,13 +604,15 @@ __device__ __forceinline__ void emit_ext(const FrameCtx<MB>& f, BeamSlab<MB>* nx
 }
 
 // WAVES = wavefronts per SIMD the register budget is cut for: 2 leaves the allocator all it
-// asks for (no spills: the fastest single workgroup), 4 halves the budget (a few dozen
-// spilled registers, each frame ~7% slower) so that twice as many utterances are resident
-// when the batch has more workgroups than the chip can hold at 2.
+// asks for (no spills: the fastest single workgroup); 3 and 4 spill a few registers (each
+// frame some per cent slower) so that more utterances are resident when the batch has more
+// workgroups than the chip can hold at 2.
 template <int LM, int THREADS, int MB, int WAVES>
 __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(WAVES, WAVES)))
 void beam_kernel(BeamArgs a) {
     constexpr int kThreads = THREADS;
+    constexpr int kWalkers = kThreads < kWaypoints ? kThreads : kWaypoints;  // back-walk batch
+    static_assert(THREADS >= 4 * kChunk, "a chunk of headers is staged 16 bytes per thread");
     constexpr int kMaxBeam = MB;
     constexpr int kHashSlots = 4 * MB;
     static_assert(THREADS >= MB, "one thread per beam entry");
@@ -1262,7 +1266,7 @@ void beam_kernel(BeamArgs a) {
             if (tid == 0) {
                 int n = 0;
                 int nd = node, dp = depth;
-                while (dp > 0 && n < kWaypoints - 1 && nd > 0 && (int64_t)nd < a.trie_stride) {
+                while (dp > 0 && n < kWalkers - 1 && nd > 0 && (int64_t)nd < a.trie_stride) {
                     wp_node[n] = nd;
                     wp_depth[n] = dp;
                     ++n;
@@ -1465,16 +1469,24 @@ hipError_t launch_beam(const int32_t* lengths, int32_t B, int32_t T, int32_t V,
     // threads, V = 32 at r = 0.01 6% slower).
     // Beam capacity: up to 128 entries the beam state takes 30 KB of LDS; beyond, the
     // 512-entry build (100 KB, one thread per entry, one workgroup per CU) is used.
-    // Residency: registers, not LDS, limit how many workgroups share a CU.  At two wavefronts
-    // per SIMD a CU holds two 256-thread workgroups (one of 512 threads); a batch with more
-    // utterances than that over the whole chip runs the build cut for four wavefronts per
-    // SIMD (measured on B = 4096, V = 32: 473 M frames/s against 287 M).
+    // Residency: at two wavefronts per SIMD a CU holds two 256-thread workgroups (one of 512
+    // threads).  A batch with more utterances than that over the whole chip is bound by
+    // instruction issue, not by one frame's latency, and small frames then run best as two
+    // wavefronts per utterance (one for the stays, one for the extensions: the other two of
+    // the four mostly repeat wave-uniform bookkeeping), with registers cut for three
+    // wavefronts per SIMD and, where a one-shot decode's beam allows, the 64-entry state
+    // (17 KB of LDS) so that more workgroups fit a CU.  Measured on B = 4096, V = 32,
+    // beam 32: 287 M frames/s with the four-wavefront build alone, 470 M with its registers
+    // cut for four wavefronts per SIMD, 564 M with two wavefronts per utterance, 679 M with
+    // the small state as well.  A streaming decode keeps the 128-entry state throughout (its
+    // carried records are laid out for it).
     const bool wide = V > 64;
     const bool large_beam = p.beam > kBeamSmall;
     int n_cu = 0;
     hipError_t qe = compute_units(&n_cu);
     if (qe != hipSuccess) return qe;
     const bool dense = (int64_t)B > (int64_t)n_cu * (wide ? 1 : 2);
+    const bool tiny_state = p.beam <= kBeamTiny && carried == nullptr;
 #define FLTOP_LAUNCH_BEAM(LM_)                                                               \
     do {                                                                                     \
         if (large_beam)                                                                      \
@@ -1486,9 +1498,12 @@ hipError_t launch_beam(const int32_t* lengths, int32_t B, int32_t T, int32_t V,
         else if (wide)                                                                       \
             hipLaunchKernelGGL((beam_kernel<LM_, kThreadsLarge, kBeamSmall, 2>),             \
                                dim3((unsigned)B), dim3(kThreadsLarge), dyn, stream, a);      \
+        else if (dense && tiny_state)                                                        \
+            hipLaunchKernelGGL((beam_kernel<LM_, kThreadsDense, kBeamTiny, 3>),              \
+                               dim3((unsigned)B), dim3(kThreadsDense), dyn, stream, a);      \
         else if (dense)                                                                      \
-            hipLaunchKernelGGL((beam_kernel<LM_, kThreadsSmall, kBeamSmall, 4>),             \
-                               dim3((unsigned)B), dim3(kThreadsSmall), dyn, stream, a);      \
+            hipLaunchKernelGGL((beam_kernel<LM_, kThreadsDense, kBeamSmall, 3>),             \
+                               dim3((unsigned)B), dim3(kThreadsDense), dyn, stream, a);      \
         else                                                                                 \
             hipLaunchKernelGGL((beam_kernel<LM_, kThreadsSmall, kBeamSmall, 2>),             \
                                dim3((unsigned)B), dim3(kThreadsSmall), dyn, stream, a);      \

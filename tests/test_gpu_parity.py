@@ -386,12 +386,15 @@ def test_more_utterances_than_one_grid_dimension_holds(dev, oracle_lib):
     assert got["stats"]["frames"] == int(ln.sum())
 
 
-@pytest.mark.parametrize("case", ["v32", "v32_lm", "v100_lm"])
+@pytest.mark.parametrize("case", ["v32", "v32_lm", "v32_beam100", "v100_lm"])
 def test_batches_larger_than_the_chip_holds_at_once(dev, oracle_lib, case):
     """More utterances than two workgroups per compute unit (one, for the 512-thread
-    build): the launcher then takes the build with the halved register budget."""
+    build): the launcher then takes the builds made for residency -- two wavefronts per
+    utterance with a 64- or 128-entry beam state for small vocabularies, the halved register
+    budget for large ones."""
     B, T, V, beam, r, lm_on = {"v32": (530, 36, 32, 32, 0.0, False),
                                "v32_lm": (600, 40, 32, 16, 1e-3, True),
+                               "v32_beam100": (520, 30, 32, 100, 1e-3, False),
                                "v100_lm": (300, 30, 100, 20, 1e-3, True)}[case]
     assert B > (256 if V > 64 else 512)
     lp = synth.random_emissions(4242 + V + B, B, T, V, flat=1.5)
@@ -402,8 +405,16 @@ def test_batches_larger_than_the_chip_holds_at_once(dev, oracle_lib, case):
     alpha, beta = (0.6, 0.4) if lm_on else (0.0, 0.0)
     want = oracle_lib.decode(lp, ln, beam, r, lm_table=lm, lm_weight=alpha,
                              insertion_bonus=beta, n_threads=8)
-    got = gpu_decode(dev, lp, ln, beam, r, lm=lm, alpha=alpha, beta=beta)
+    got = gpu_decode(dev, lp, ln, beam, r, lm=lm, alpha=alpha, beta=beta, nbest=True)
     assert_parity(got, want[0], want[1], want[2], case)
+    # the whole final beam of the first utterance, in rank order
+    ref = oracle_lib.decode_beam(lp[0], beam, r, lm_table=lm, lm_weight=alpha,
+                                 insertion_bonus=beta, max_entries=beam)
+    assert len(got["nbest"][0]) == len(ref)
+    for (gt, gpb, gpnb), (wt, wpb, wpnb) in zip(got["nbest"][0], ref):
+        assert gt == wt
+        for g, w_ in ((gpb, wpb), (gpnb, wpnb)):
+            assert g == w_ or abs(g - w_) <= 1e-9
 
 
 def test_same_input_twice_gives_identical_bytes(dev):

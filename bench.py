@@ -273,6 +273,80 @@ def batch_scaling(torch, binding, job, r, factors=(1, 4, 16, 64)):
     return out
 
 
+def streaming_latency(torch, binding, synth, w, r, dev, chunk_frames=25, batches=(1, None)):
+    """Chunked decode with carried beam state (the paper's real-time motivation, Sec. 1):
+    the workload's utterances arrive `chunk_frames` frames at a time (0.5 s of audio at 50
+    frames/s); per-call latency of one chunk, and the whole utterances against one call."""
+    lp_host, ln_host = synth.make_emissions(w)
+    lm = torch.from_numpy(synth.make_bigram_lm(w.V)).to(dev) if w.use_lm else None
+    out = []
+    for nb in batches:
+        B = w.B if nb is None else min(nb, w.B)
+        lp = torch.from_numpy(lp_host[:B]).to(dev)
+        ln = ln_host[:B]
+        st = binding.Stream(B, w.T, chunk_frames, w.V, w.beam, r, dev, lm_table=lm,
+                            lm_weight=w.lm_weight, insertion_bonus=w.insertion_bonus)
+        pieces = []
+        for t0 in range(0, w.T, chunk_frames):
+            tc = min(chunk_frames, w.T - t0)
+            pieces.append((lp[:, t0:t0 + tc].contiguous(),
+                           torch.from_numpy((ln - t0).clip(0, tc).astype("int32")).to(dev)))
+
+        def whole(i):
+            st.begin()
+            for piece, piece_len in pieces:
+                st.feed(piece, piece_len)
+
+        total = event_times_ms(torch, whole, 5)
+        # one chunk in the middle of the utterances, state as the preceding chunks left it
+        mid = len(pieces) // 2
+        st.begin()
+        for piece, piece_len in pieces[:mid]:
+            st.feed(piece, piece_len)
+        torch.cuda.synchronize()
+        saved = st.state.clone()
+
+        def one(i):
+            st.state.copy_(saved)
+            st.feed(*pieces[mid])
+
+        def restore_only(i):
+            st.state.copy_(saved)
+
+        both = event_times_ms(torch, one, 20)
+        restore = event_times_ms(torch, restore_only, 20)
+        per_chunk = max(0.0, sorted(both)[len(both) // 2] - sorted(restore)[len(restore) // 2])
+        frames = int(ln.sum())
+        tot = sum(total) / len(total)
+        out.append({"B": B, "chunk_frames": chunk_frames, "chunks": len(pieces),
+                    "chunk_latency_us": round(per_chunk * 1e3, 1),
+                    "whole_ms": round(tot, 4),
+                    "frames_per_s": round(frames / (tot * 1e-3), 1),
+                    "audio_seconds_per_chunk": chunk_frames / synth.FRAMES_PER_SECOND})
+        del st, lp, pieces, saved
+        torch.cuda.empty_cache()
+    return out
+
+
+def other_workloads(torch, binding, synth, dev, skip):
+    """Whole-decode time of the remaining named workloads at their first threshold."""
+    out = []
+    for name, ww in synth.WORKLOADS.items():
+        if name == skip:
+            continue
+        job = Job(torch, binding, synth, ww, dev)
+        rr = ww.rel_thresholds[0]
+        pp = job.params(rr)
+        ms = event_times_ms(torch, lambda i: job.decode(pp), 5)
+        avg = sum(ms) / len(ms)
+        out.append({"workload": name, "B": ww.B, "T": ww.T, "V": ww.V, "beam": ww.beam,
+                    "rel_threshold": rr, "lm": bool(ww.use_lm), "frames": job.frames,
+                    "ms": round(avg, 4), "frames_per_s": round(job.frames / (avg * 1e-3), 1)})
+        del job
+        torch.cuda.empty_cache()
+    return out
+
+
 def cpu_baseline(synth, w, r, frames_budget_s=12.0):
     import oracle
     threads = max(1, min(16, os.cpu_count() or 1))
@@ -475,6 +549,7 @@ def main():
             torch, binding, wide_job, 25.0)
         del wide_job
         result["batch_scaling"] = batch_scaling(torch, binding, job, r)
+        result["streaming"] = streaming_latency(torch, binding, synth, w, r, dev)
         result["paper_context"] = ("paper reports 10.5x runtime speedup and 2.78x fewer beams "
                                    "(FLToP N=4,R=0.007 vs all-32-token baseline) for a CPU "
                                    "flashlight/KenLM decoder on LibriSpeech, wav2vec2-large "
@@ -490,6 +565,7 @@ def main():
             torch.cuda.empty_cache()
         result["roofline_emission_read"] = reads[0]
         result["emission_read_other_workloads"] = reads[1:]
+        result["other_workloads"] = other_workloads(torch, binding, synth, dev, w.name)
 
     if not args.skip_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(synth, w, r)

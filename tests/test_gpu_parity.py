@@ -455,6 +455,33 @@ def test_same_input_twice_gives_identical_bytes(dev):
         assert runs[0][key] == runs[1][key], key
 
 
+def test_concurrent_decodes_on_separate_streams(dev, oracle_lib):
+    """The library keeps no decoding state: calls on different HIP streams with their own
+    workspaces may overlap on the GPU."""
+    cases = []
+    for i, (B, T, V, beam, r) in enumerate([(40, 120, 32, 32, 0.01), (24, 90, 32, 64, 0.0),
+                                            (16, 60, 300, 16, 1e-3), (64, 150, 32, 8, 0.05)]):
+        lp = synth.random_emissions(7000 + i, B, T, V, flat=2.0)
+        ln = np.random.default_rng(7000 + i).integers(T // 2, T + 1, size=B).astype(np.int32)
+        cases.append((lp, ln, beam, r, torch.from_numpy(lp).to(dev), torch.from_numpy(ln).to(dev),
+                      binding.alloc_workspace(B, T, V, beam, dev), torch.cuda.Stream()))
+    want = [oracle_lib.decode(lp, ln, beam, r, n_threads=4) for lp, ln, beam, r, *_ in cases]
+    torch.cuda.synchronize()
+    for rep in range(3):  # three rounds of four overlapping decodes
+        outs = []
+        for lp, ln, beam, r, lp_d, ln_d, ws, side in cases:
+            with torch.cuda.stream(side):
+                outs.append(binding.decode(lp_d, ln_d, beam, r, workspace=ws, want_stats=True))
+        torch.cuda.synchronize()
+        for i, out in enumerate(outs):
+            lens = out["lengths"].cpu().numpy()
+            toks = out["tokens"].cpu().numpy()
+            got = {"tokens": [toks[b, :lens[b]].tolist() for b in range(len(lens))],
+                   "scores": out["scores"].cpu().numpy(),
+                   "stats": binding.stats_dict(out["stats"])}
+            assert_parity(got, want[i][0], want[i][1], want[i][2], f"round {rep} stream {i}")
+
+
 def test_all_utterances_empty(dev, oracle_lib):
     lp = np.full((3, 5, 8), np.nan, dtype=np.float32)
     ln = np.zeros(3, dtype=np.int32)

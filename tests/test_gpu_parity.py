@@ -386,7 +386,7 @@ def test_more_utterances_than_one_grid_dimension_holds(dev, oracle_lib):
     assert got["stats"]["frames"] == int(ln.sum())
 
 
-@pytest.mark.parametrize("case", ["v32", "v32_lm", "v32_beam100", "v100_lm"])
+@pytest.mark.parametrize("case", ["v32", "v32_lm", "v32_beam100", "v100_lm", "v100_b600"])
 def test_batches_larger_than_the_chip_holds_at_once(dev, oracle_lib, case):
     """More utterances than two workgroups per compute unit (one, for the 512-thread
     build): the launcher then takes the builds made for residency -- two wavefronts per
@@ -395,7 +395,8 @@ def test_batches_larger_than_the_chip_holds_at_once(dev, oracle_lib, case):
     B, T, V, beam, r, lm_on = {"v32": (530, 36, 32, 32, 0.0, False),
                                "v32_lm": (600, 40, 32, 16, 1e-3, True),
                                "v32_beam100": (520, 30, 32, 100, 1e-3, False),
-                               "v100_lm": (300, 30, 100, 20, 1e-3, True)}[case]
+                               "v100_lm": (300, 30, 100, 20, 1e-3, True),
+                               "v100_b600": (600, 24, 100, 20, 1e-3, False)}[case]
     assert B > (256 if V > 64 else 512)
     lp = synth.random_emissions(4242 + V + B, B, T, V, flat=1.5)
     rng = np.random.default_rng(B)

@@ -344,7 +344,8 @@ struct FrameCtx {
     bool collapsed;          // blank-only frames came last: read p_b as total, p_nb as -inf
     int nb0;                 // 1 if blank survived (it is record 0 then)
     int Knb;                 // non-blank survivors
-    uint32_t div_magic;      // from the frame header: umulhi(e, div_magic) == e / Knb (Knb > 1)
+    uint32_t div_magic;      // from the frame header: umulhi(e, div_magic) is e / Knb, or one
+                             // more when e is large (Knb > 1)
     uint64_t Rk;             // key of an upper bound of every candidate score
     // survivors 0..5 as plain scalars (an indexed private array would live in scratch)
     int32_t t0, t1, t2, t3, t4, t5;
@@ -428,8 +429,14 @@ __device__ __forceinline__ double lm_term(const FrameCtx<MB>& f, int32_t prev, i
 template <int LM, int MB>
 __device__ __forceinline__ uint64_t eval_ext(const FrameCtx<MB>& f, int e, int& src_entry,
                                              int32_t& tok) {
-    const int i = f.Knb > 1 ? (int)__umulhi((uint32_t)e, f.div_magic) : e;
-    const int k = e - i * f.Knb;
+    // the reciprocal is rounded up, so for large e the quotient can come out one too large
+    // (never more): a negative remainder says so
+    int i = f.Knb > 1 ? (int)__umulhi((uint32_t)e, f.div_magic) : e;
+    int k = e - i * f.Knb;
+    if (k < 0) {
+        --i;
+        k += f.Knb;
+    }
     double lps;
     const int32_t s = surv_tok_lp(f, f.nb0 + k, lps);
     src_entry = i;

@@ -29,7 +29,8 @@ struct alignas(64) FrameHdr {
     int32_t has_blank;   // 1 if token 0 survived (it is survivor 0 then), else 0
     float top;           // max_v lp[t][v]
     uint32_t div_magic;  // floor((2^32 - 1) / n) + 1 for n = count - has_blank > 1, else 0:
-                         // umulhi(e, div_magic) == e / n for every e < 2^19
+                         // umulhi(e, div_magic) == e / n for every e < 2^19, and at most one
+                         // more than that for any larger e below 2^32
     Survivor first[kInlineSurvivors];  // survivors 0..min(count,6)-1, ascending token; unused
                                        // places hold (token -1, log-prob -inf)
 };

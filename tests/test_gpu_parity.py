@@ -483,6 +483,28 @@ def test_concurrent_decodes_on_separate_streams(dev, oracle_lib):
             assert_parity(got, want[i][0], want[i][1], want[i][2], f"round {rep} stream {i}")
 
 
+def test_two_million_candidates_per_frame(dev, oracle_lib):
+    """512 beam entries x 4095 tokens: candidate numbers pass 2^20, where the reciprocal
+    that splits a number into (entry, token) rounds to the next entry for the last token
+    of an entry.  Frame 2 makes exactly that token the best one."""
+    V, beam = binding.MAX_VOCAB, binding.MAX_BEAM
+    lp = synth.random_emissions(4098, 1, 4, V, flat=1.0)
+    lp[0, 2, V - 1] += 9.0  # rows need not be normalised
+    ln = np.array([4], dtype=np.int32)
+    want = oracle_lib.decode(lp, ln, beam, 0.0)
+    assert want[0][0][-2:].count(V - 1) >= 1  # the boosted token is on the best path
+    got = gpu_decode(dev, lp, ln, beam, 0.0, nbest=True)
+    assert_parity(got, want[0], want[1], want[2], "V4096 beam512, last token boosted")
+    ref = oracle_lib.decode_beam(lp[0], beam, 0.0, max_entries=beam)
+    assert [e[0] for e in got["nbest"][0]] == [e[0] for e in ref]
+    # a plain case whose candidate count was off by one
+    lp = synth.random_emissions(100 * V + 1, 1, 6, V, flat=3.0)
+    ln = np.array([6], dtype=np.int32)
+    want = oracle_lib.decode(lp, ln, beam, 0.0)
+    got = gpu_decode(dev, lp, ln, beam, 0.0)
+    assert_parity(got, want[0], want[1], want[2], "V4096 beam512 six frames")
+
+
 def test_all_utterances_empty(dev, oracle_lib):
     lp = np.full((3, 5, 8), np.nan, dtype=np.float32)
     ln = np.zeros(3, dtype=np.int32)

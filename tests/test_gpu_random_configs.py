@@ -1,0 +1,80 @@
+"""GPU parity on seeded random configurations: vocabulary, beam, threshold, top-N, score
+window, LM, tie-heavy (coarsely quantised) emissions and ragged lengths are drawn together,
+so that corners no hand-written case names get visited.  Same bar as the other parity
+tests: tokens, lengths and integer statistics exact, scores within 1e-4, per-frame beam
+sizes exact."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2510_09085_amd import binding, synth
+
+pytestmark = pytest.mark.gpu
+
+SCORE_TOL = 1e-4
+VOCABS = [2, 3, 7, 32, 33, 64, 65, 100, 500, 1024, 2933, 4096]
+BEAMS = [1, 2, 7, 32, 64, 65, 128, 129, 300, 512]
+
+
+def draw_case(rng, seed):
+    V = int(rng.choice(VOCABS))
+    beam = int(rng.choice(BEAMS))
+    r = float(rng.choice([0.0, 0.0, 1e-4, 1e-3, 0.01, 0.1, 0.5, 1.0]))
+    top_n = int(rng.choice([0, 0, 1, 2, 4, 7, 50]))
+    window = float(rng.choice([0.0, 0.0, 0.5, 3.0, 25.0]))
+    use_lm = bool(rng.random() < 0.4)
+    flat = float(rng.choice([0.3, 1.0, 2.0, 4.0]))
+    quantised = bool(rng.random() < 0.25)
+    # keep the oracle's work per case to a few million candidate updates
+    per_frame = beam * (V if r < 1e-3 and top_n == 0 else min(V, 16))
+    T = int(rng.integers(2, int(max(2, min(60, 6e6 // per_frame))) + 1))
+    B = int(rng.choice([1, 2, 5]))
+    if per_frame * T * B > 3e7:
+        B = 1
+    lp = synth.random_emissions(seed, B, T, V, flat=flat)
+    if quantised:
+        lp = (np.round(lp * 2) / 2).astype(np.float32)
+    ln = rng.integers(0, T + 1, size=B).astype(np.int32)
+    ln[0] = T
+    lm = synth.make_bigram_lm(V, seed=seed) if use_lm else None
+    if lm is not None and quantised:
+        lm = np.round(lm).astype(np.float32)
+    label = (f"B{B} T{T} V{V} beam{beam} r{r} N{top_n} window{window} lm{use_lm} "
+             f"flat{flat} quantised{quantised}")
+    return lp, ln, beam, r, top_n, window, lm, label
+
+
+@pytest.mark.parametrize("seed0", [11, 12, 13])
+def test_random_configurations(oracle_lib, seed0):
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    dev = torch.device("cuda:0")
+    rng = np.random.default_rng(seed0)
+    for case in range(60):
+        lp, ln, beam, r, top_n, window, lm, label = draw_case(rng, seed0 * 1000 + case)
+        label = f"seed {seed0} case {case}: {label}"
+        okw = dict(top_n=top_n, beam_threshold=window)
+        gkw = dict(okw)
+        if lm is not None:
+            okw.update(lm_table=lm, lm_weight=0.7, insertion_bonus=0.3)
+            gkw.update(lm_table=torch.from_numpy(lm).to(dev), lm_weight=0.7, insertion_bonus=0.3)
+        want_tok, want_sc, want_st = oracle_lib.decode(lp, ln, beam, r, n_threads=8, traces=True,
+                                                       **okw)
+        out = binding.decode(torch.from_numpy(lp).to(dev), torch.from_numpy(ln).to(dev), beam, r,
+                             want_stats=True, want_traces=True, **gkw)
+        torch.cuda.synchronize()
+        lens = out["lengths"].cpu().numpy()
+        toks = out["tokens"].cpu().numpy()
+        for b in range(len(ln)):
+            assert toks[b, :lens[b]].tolist() == want_tok[b], f"{label}: utterance {b}"
+        ws = np.asarray(want_sc, dtype=np.float64).astype(np.float32)
+        gs = out["scores"].cpu().numpy()
+        fin = np.isfinite(ws)
+        assert np.all(np.abs(gs[fin].astype(np.float64) - ws[fin]) <= SCORE_TOL), label
+        assert np.all(gs[~fin] == ws[~fin]), label
+        st = binding.stats_dict(out["stats"])
+        for key in ("frames", "sum_survivors", "sum_candidates", "peak_candidates", "sum_beam"):
+            assert st[key] == want_st[key], (label, key)
+        assert st["overflow_drops"] == 0, label
+        fb = out["frame_beam"].cpu().numpy()
+        for b in range(len(ln)):
+            np.testing.assert_array_equal(fb[b, :ln[b]], want_st["frame_beam"][b, :ln[b]], label)

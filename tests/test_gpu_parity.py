@@ -505,6 +505,41 @@ def test_two_million_candidates_per_frame(dev, oracle_lib):
     assert_parity(got, want[0], want[1], want[2], "V4096 beam512 six frames")
 
 
+def _one_token_per_frame(seed, B, T, V):
+    """Peaked emissions whose arg-max path names a new token in every frame."""
+    rng = np.random.default_rng(seed)
+    logits = rng.standard_normal((B, T, V))
+    tok = 1 + (np.arange(T)[None, :] + rng.integers(0, V - 1, size=(B, 1))) % (V - 1)
+    np.put_along_axis(logits, tok[:, :, None], 9.0, axis=2)
+    logits -= np.log(np.exp(logits).sum(axis=2, keepdims=True))
+    return logits.astype(np.float32)
+
+
+def test_transcripts_longer_than_one_back_walk_batch(dev, oracle_lib):
+    """The best prefix is read back in batches of way-points (8 tokens each, one thread per
+    way-point): 6000 tokens need several batches, and so do 1300 tokens in the 128-thread
+    build that large batches run."""
+    lp = _one_token_per_frame(61, 2, 6000, 8)
+    ln = np.array([6000, 4100], dtype=np.int32)
+    want = oracle_lib.decode(lp, ln, 4, 0.01, n_threads=2, traces=True)
+    assert len(want[0][0]) > 5900
+    out = binding.decode(torch.from_numpy(lp).to(dev), torch.from_numpy(ln).to(dev), 4, 0.01,
+                         want_traces=True)
+    torch.cuda.synchronize()
+    lens = out["lengths"].cpu().numpy()
+    for b in range(2):
+        assert out["tokens"][b, :lens[b]].cpu().tolist() == want[0][b]
+        assert out["token_frames"][b, :lens[b]].cpu().tolist() == want[2]["token_frames"][b]
+    B = 520
+    lp = _one_token_per_frame(62, B, 1300, 5)
+    ln = np.full(B, 1300, dtype=np.int32)
+    ln[1::3] = 1100
+    want = oracle_lib.decode(lp, ln, 2, 0.01, n_threads=8)
+    assert min(len(t) for t in want[0]) > 1050
+    got = gpu_decode(dev, lp, ln, 2, 0.01)
+    assert_parity(got, want[0], want[1], want[2], "520 long transcripts")
+
+
 def test_all_utterances_empty(dev, oracle_lib):
     lp = np.full((3, 5, 8), np.nan, dtype=np.float32)
     ln = np.zeros(3, dtype=np.int32)

@@ -38,6 +38,9 @@ def parse_args():
                     help="run only that stage a few times (plus, for prune, a plain device copy "
                          "of known size for calibration): the program to put under "
                          "`rocprofv3 --pmc ...`")
+    ap.add_argument("--probe-replicas", type=int, default=1,
+                    help="with --counter-probe search: decode the workload's utterances this "
+                         "many times over in one batch (large-batch regime)")
     return ap.parse_args()
 
 
@@ -462,12 +465,27 @@ def counter_probe(args, torch, binding, synth, dev):
         out.update({"prune_launches": n + 1, "emission_bytes_per_launch": prune_bytes(w, st),
                     "written_bytes_approx": prune_written_bytes(st)})
     else:
+        import dataclasses
+        k = max(1, args.probe_replicas)
         job = Job(torch, binding, synth, w, dev)
+        if k > 1:  # the same utterances k times over, as one batch
+            big = Job.__new__(Job)
+            big.torch, big.binding = torch, binding
+            big.w = dataclasses.replace(w, B=w.B * k)
+            big.lp = [job.lp[0].repeat(k, 1, 1).contiguous()]
+            big.ln = job.ln.repeat(k).contiguous()
+            big.lm, big.frames = job.lm, job.frames * k
+            big.ws = binding.alloc_workspace(w.B * k, w.T, w.V, w.beam, dev)
+            big.tok = torch.full((w.B * k, w.T), -1, dtype=torch.int32, device=dev)
+            big.olen = torch.zeros(w.B * k, dtype=torch.int32, device=dev)
+            big.sc = torch.zeros(w.B * k, dtype=torch.float32, device=dev)
+            big.stats = job.stats
+            job = big
         p = job.params(r)
         job.prune(r)
         for _ in range(5):
             job.search(p)
-        out.update({"search_launches": 5, "frames": job.frames})
+        out.update({"search_launches": 5, "frames": job.frames, "B": job.w.B})
     torch.cuda.synchronize()
     # calibration: a plain device-to-device copy of 256 MiB reads and writes 256 MiB
     src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).random_(0, 255)

@@ -172,8 +172,10 @@ int fltop_ctc_unpack_survivors(const void* workspace, size_t workspace_bytes,
  * in chunks gives exactly what fltop_ctc_decode gives on the whole utterance.
  *
  *   state    dev, 256-byte aligned, >= fltop_ctc_stream_state_bytes(B, T_total, beam): per
- *            utterance the carried beam, then the prefix trie for up to T_total frames.
- *            Caller-owned; one state per batch of streams; the same B and beam in every call.
+ *            utterance the carried beam, then the prefix trie for up to T_total frames,
+ *            then a note of which prefix stands behind every transcript token written so
+ *            far.  Caller-owned; one state per batch of streams; the same B and beam in
+ *            every call.
  *   fltop_ctc_stream_begin   resets every stream of the batch to the empty prefix.
  *   fltop_ctc_stream_decode  consumes the next chunk: logprobs dev [B,T_chunk,V], lengths
  *            dev [B] = valid frames of this chunk per stream (0 for a stream that has
@@ -183,6 +185,10 @@ int fltop_ctc_unpack_survivors(const void* workspace, size_t workspace_bytes,
  *            [B,T_total]; the traces and the n-best token rows of params, if given, are
  *            [B,T_total] / [B,beam,T_total] and indexed by the frame number since the
  *            stream began.  stats count this chunk only.
+ *            While out_tokens (and params->out_token_frames) stay the same buffers from
+ *            call to call, with their contents left alone, a call rewrites only the part of
+ *            a transcript that has changed, so its cost does not grow with the transcript;
+ *            other buffers are noticed and written in full.
  * Calls on one state must be ordered (same stream, or synchronised by the caller). */
 size_t fltop_ctc_stream_state_bytes(int32_t B, int32_t T_total, int32_t beam);
 int fltop_ctc_stream_begin(void* state, size_t state_bytes, int32_t B, int32_t T_total,

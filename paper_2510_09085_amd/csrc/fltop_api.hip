@@ -166,7 +166,7 @@ extern "C" int fltop_ctc_stream_begin(void* state, size_t state_bytes, int32_t B
     if (rc != FLTOP_OK) return rc;
     const fltop::StreamSpace sp = fltop::carve_stream(state, B, T_total, beam);
     hipError_t e =
-        fltop::launch_stream_begin(sp.records, B, beam, static_cast<hipStream_t>(hip_stream));
+        fltop::launch_stream_begin(sp, B, beam, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? FLTOP_OK : FLTOP_ERR_HIP;
 }
 

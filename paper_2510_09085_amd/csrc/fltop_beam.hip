@@ -93,8 +93,11 @@ struct StreamState {
     int32_t frames_done;  // frames decoded so far (= trie frame index of the next one)
     int32_t n_live;
     int32_t collapsed;
-    int32_t pad;
+    int32_t out_len;      // length of the transcript as last written
     double bias, kmax, kmin;
+    // where the transcript and its entry frames were last written: the record of trie nodes
+    // behind the written tokens holds for those rows only
+    uint64_t out_tokens_at, out_frames_at;
     BeamSlab<MB> slab;
     int32_t par[MB];
     int32_t first_kid[MB];
@@ -119,6 +122,7 @@ struct BeamArgs {
     int32_t B, T, V, beam;
     int32_t lm_in_lds;  // 1: table staged into LDS
     void* stream;          // streaming decode: array of StreamState<MB> (NULL for a one-shot decode)
+    int32_t* out_nodes;    // streaming: [B, t_total] trie node behind each written token
     int32_t t_total;       // streaming: frames the trie and the output rows are sized for
     int32_t out_stride;    // row length of out_tokens and of the traces
     double beam_window;  // SelectTopK's score window below the frame's best candidate; <= 0: off
@@ -737,7 +741,12 @@ void beam_kernel(BeamArgs a) {
     double bias = 0.0;       // log-mass of the blank-only frames, common to every entry
     bool collapsed = false;  // blank-only frames since the beam was last written
     double kmax_v = 0.0, kmin_v = 0.0;  // bounds of the best / worst score (without bias)
+    int prev_out_len = 0;       // streaming: length of the transcript the last call wrote ...
+    uint64_t prev_tokens_at = 0, prev_frames_at = 0;  // ... and the rows it wrote it to
     if (carried) {
+        prev_out_len = carried->out_len;
+        prev_tokens_at = carried->out_tokens_at;
+        prev_frames_at = carried->out_frames_at;
         n_live = carried->n_live;
         bias = carried->bias;
         collapsed = carried->collapsed != 0;
@@ -1263,17 +1272,29 @@ void beam_kernel(BeamArgs a) {
     }
     // Back-walk: thread 0 follows the every-8th-level links and records way-points; then
     // one thread per way-point walks the (at most 8) parents down to the next way-point.
+    // A streaming decode remembers the trie node behind every token it wrote: where the walk
+    // meets the node that is already written at that position, everything before it is in
+    // place (a node's ancestors never change), so a call rewrites only what has changed.
+    int32_t* const out_row = a.out_tokens + (int64_t)b * a.out_stride;
+    int32_t* const born_row =
+        a.out_token_frames ? a.out_token_frames + (int64_t)b * a.out_stride : nullptr;
+    int32_t* const wrote = a.out_nodes ? a.out_nodes + (int64_t)b * a.out_stride : nullptr;
+    const bool same_rows = wrote && prev_tokens_at == (uint64_t)(uintptr_t)out_row &&
+                           prev_frames_at == (uint64_t)(uintptr_t)born_row;
+    const int new_out_len = best >= 0 ? fin.plen[best] : 0;
     if (best >= 0) {
         int node = fin.node[best];
-        int depth = fin.plen[best];
-        int32_t* dst = a.out_tokens + (int64_t)b * a.out_stride;
-        int32_t* born =
-            a.out_token_frames ? a.out_token_frames + (int64_t)b * a.out_stride : nullptr;
+        int depth = new_out_len;
         while (depth > 0) {  // uniform: node/depth are re-read from LDS after each batch
             if (tid == 0) {
                 int n = 0;
                 int nd = node, dp = depth;
+                bool met = false;
                 while (dp > 0 && n < kWalkers - 1 && nd > 0 && (int64_t)nd < a.trie_stride) {
+                    if (same_rows && wrote[dp - 1] == nd) {
+                        met = true;
+                        break;
+                    }
                     wp_node[n] = nd;
                     wp_depth[n] = dp;
                     ++n;
@@ -1281,9 +1302,10 @@ void beam_kernel(BeamArgs a) {
                     nd = tn.xup;
                     dp = (dp - 1) & ~7;
                 }
-                const bool ok = nd > 0 && (int64_t)nd < a.trie_stride;
-                wp_node[n] = nd;  // where the next batch starts
-                wp_depth[n] = ok ? dp : 0;
+                const bool ok = !met && nd > 0 && (int64_t)nd < a.trie_stride;
+                wp_node[n] = nd;             // where the next batch starts ...
+                wp_depth[n] = met ? dp : (ok ? dp : 0);  // ... and the last walker stops
+                sh_blcount = ok ? dp : 0;    // depth left for the next batch
                 sh_nnew = n;
             }
             __syncthreads();
@@ -1293,18 +1315,22 @@ void beam_kernel(BeamArgs a) {
                 int dp = wp_depth[tid];
                 const int stop = wp_depth[tid + 1];
                 while (dp > stop && nd > 0 && (int64_t)nd < a.trie_stride) {
+                    if (same_rows && wrote[dp - 1] == nd) break;
                     const TrieNode tn = trie[nd];
-                    dst[dp - 1] = tn.tok;
-                    if (born) born[dp - 1] = (nd - 1) / beam;  // node id = 1 + frame * beam + slot
+                    out_row[dp - 1] = tn.tok;
+                    if (born_row) born_row[dp - 1] = (nd - 1) / beam;  // node id = 1 + frame * beam + slot
+                    if (wrote) wrote[dp - 1] = nd;
                     nd = tn.parent;
                     --dp;
                 }
             }
             node = wp_node[n];
-            depth = wp_depth[n];
+            depth = sh_blcount;
             __syncthreads();
         }
     }
+    if (wrote)  // positions the shorter transcript no longer covers
+        for (int q = new_out_len + tid; q < prev_out_len; q += kThreads) wrote[q] = -1;
 
     // ---- optional: the whole final beam in rank order ---------------------------------
     if (a.nbest_count) {
@@ -1343,6 +1369,9 @@ void beam_kernel(BeamArgs a) {
         for (int i = tid; i < 4 * kMaxBeam; i += kThreads) ldst[i] = lsrc[i];
         if (tid == 0) {
             carried->frames_done = t_base + len;
+            carried->out_len = new_out_len;
+            carried->out_tokens_at = (uint64_t)(uintptr_t)out_row;
+            carried->out_frames_at = (uint64_t)(uintptr_t)born_row;
             carried->n_live = n_live;
             carried->collapsed = collapsed ? 1 : 0;
             carried->bias = bias;
@@ -1354,9 +1383,14 @@ void beam_kernel(BeamArgs a) {
 
 // A fresh stream: the empty prefix with score 0, no links, no frames seen.
 template <int MB>
-__global__ __launch_bounds__(kThreadsSmall) void stream_begin_kernel(StreamState<MB>* st, int32_t B) {
+__global__ __launch_bounds__(kThreadsSmall) void stream_begin_kernel(StreamState<MB>* st, int32_t B,
+                                                                     int32_t* out_nodes,
+                                                                     int64_t n_out_nodes) {
     constexpr int kThreads = kThreadsSmall;
     constexpr int kMaxBeam = MB;
+    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n_out_nodes;
+         i += (int64_t)gridDim.x * kThreads)
+        out_nodes[i] = -1;
     for (int32_t b = blockIdx.x; b < B; b += gridDim.x) {
         StreamState<MB>* s = st + b;
         uint32_t* words = reinterpret_cast<uint32_t*>(s);
@@ -1402,14 +1436,17 @@ size_t stream_record_bytes(int32_t beam) {
     return beam <= kBeamSmall ? sizeof(StreamState<kBeamSmall>) : sizeof(StreamState<kBeamLarge>);
 }
 
-hipError_t launch_stream_begin(void* records, int32_t B, int32_t beam, hipStream_t stream) {
+hipError_t launch_stream_begin(const StreamSpace& sp, int32_t B, int32_t beam, hipStream_t stream) {
     const dim3 grid((unsigned)(B < 1024 ? B : 1024));
+    const int64_t n_out_nodes = (int64_t)B * sp.t_total;
     if (beam <= kBeamSmall)
         hipLaunchKernelGGL(stream_begin_kernel<kBeamSmall>, grid, dim3(kThreadsSmall), 0, stream,
-                           static_cast<StreamState<kBeamSmall>*>(records), B);
+                           static_cast<StreamState<kBeamSmall>*>(sp.records), B, sp.out_nodes,
+                           n_out_nodes);
     else
         hipLaunchKernelGGL(stream_begin_kernel<kBeamLarge>, grid, dim3(kThreadsSmall), 0, stream,
-                           static_cast<StreamState<kBeamLarge>*>(records), B);
+                           static_cast<StreamState<kBeamLarge>*>(sp.records), B, sp.out_nodes,
+                           n_out_nodes);
     return hipGetLastError();
 }
 
@@ -1444,6 +1481,7 @@ hipError_t launch_beam(const int32_t* lengths, int32_t B, int32_t T, int32_t V,
     a.trie = carried ? carried->trie : ws.trie;
     a.trie_stride = carried ? carried->trie_stride : ws.trie_stride;
     a.stream = carried ? carried->records : nullptr;
+    a.out_nodes = carried ? carried->out_nodes : nullptr;
     a.t_total = carried ? carried->t_total : T;
     a.out_stride = carried ? carried->t_total : T;
     a.lm_table = p.lm_table;

@@ -91,6 +91,8 @@ struct StreamSpace {
     void* records;
     TrieNode* trie;
     int64_t trie_stride;  // nodes per utterance: t_total * beam + 1
+    int32_t* out_nodes;   // [B, t_total]: trie node behind each token of the transcript as it was
+                          // last written (-1 beyond its length)
     int32_t t_total;
     size_t bytes;
 };
@@ -102,14 +104,17 @@ inline StreamSpace carve_stream(void* base, int32_t B, int32_t t_total, int32_t 
     s.t_total = t_total;
     s.trie_stride = (int64_t)t_total * beam + 1;
     const size_t off_trie = align_up((size_t)B * stream_record_bytes(beam), 256);
-    s.bytes = align_up(off_trie + (size_t)B * (size_t)s.trie_stride * sizeof(TrieNode), 256);
+    const size_t off_nodes =
+        align_up(off_trie + (size_t)B * (size_t)s.trie_stride * sizeof(TrieNode), 256);
+    s.bytes = align_up(off_nodes + (size_t)B * (size_t)t_total * sizeof(int32_t), 256);
     char* p = static_cast<char*>(base);
     s.records = p;
     s.trie = p ? reinterpret_cast<TrieNode*>(p + off_trie) : nullptr;
+    s.out_nodes = p ? reinterpret_cast<int32_t*>(p + off_nodes) : nullptr;
     return s;
 }
 
-hipError_t launch_stream_begin(void* records, int32_t B, int32_t beam, hipStream_t stream);
+hipError_t launch_stream_begin(const StreamSpace& sp, int32_t B, int32_t beam, hipStream_t stream);
 hipError_t launch_log_add(const double* a, const double* b, double* out, int64_t n,
                           hipStream_t stream);
 

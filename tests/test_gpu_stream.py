@@ -151,6 +151,39 @@ def test_chunked_decode_of_a_batch_larger_than_the_chip_holds(dev, oracle_lib):
     check_final(got, want, ln, "520 streams in chunks of 20")
 
 
+def test_transcript_is_rewritten_only_where_it_changed(dev, oracle_lib):
+    """A streaming decode keeps the trie node behind every token it has written and stops a
+    rewrite where it meets one.  Partial transcripts after every chunk (they grow, switch
+    and now and then shrink on flat emissions) must equal a fresh decode of the frames so
+    far; changing the output rows between calls must give a full rewrite."""
+    B, T, V, beam, r, chunk = 6, 60, 3, 16, 0.0, 1
+    lp = synth.random_emissions(106, B, T, V, flat=0.3)
+    ln = np.array([60, 60, 60, 41, 60, 7], dtype=np.int32)
+    st = binding.Stream(B, T, chunk, V, beam, r, dev, want_traces=True)
+    spare_tokens = torch.full_like(st.tokens, -7)
+    shrank = 0
+    prev = None
+    for t0 in range(0, T, chunk):
+        if t0 == 30:  # from here on the transcripts go to other rows
+            st.tokens = spare_tokens
+        piece_len = np.clip(ln - t0, 0, chunk).astype(np.int32)
+        st.feed(torch.from_numpy(np.ascontiguousarray(lp[:, t0:t0 + chunk])).to(dev),
+                torch.from_numpy(piece_len).to(dev))
+        torch.cuda.synchronize()
+        seen = np.minimum(ln, t0 + chunk).astype(np.int32)
+        want = oracle_lib.decode(lp[:, :t0 + chunk], seen, beam, r, traces=True, n_threads=4)
+        lens = st.lengths.cpu().numpy()
+        toks = st.tokens.cpu().numpy()
+        tf = st.token_frames.cpu().numpy()
+        for b in range(B):
+            assert toks[b, :lens[b]].tolist() == want[0][b], f"after {t0 + chunk} frames, b={b}"
+            assert tf[b, :lens[b]].tolist() == want[2]["token_frames"][b], f"frames, b={b}"
+        if prev is not None:
+            shrank += int((lens < prev).sum())
+        prev = lens.copy()
+    assert shrank > 0, "the case is meant to contain transcripts that get shorter"
+
+
 def test_stream_argument_errors(dev):
     assert binding.load().fltop_ctc_stream_state_bytes(0, 10, 4) == 0
     assert binding.load().fltop_ctc_stream_state_bytes(2, 10, binding.MAX_BEAM + 1) == 0

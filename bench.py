@@ -276,41 +276,49 @@ def batch_scaling(torch, binding, job, r, factors=(1, 4, 16, 64)):
     return out
 
 
-def concurrent_streams(torch, binding, job, r, n_streams=4, reps=10):
+def concurrent_streams(torch, binding, job, r, n_streams=4, reps=10, attempts=2):
     """Independent batches decoded at the same time on separate HIP streams (each with its
-    own workspace and outputs): how a server fills the chip when single batches are small."""
+    own workspace and outputs): how a server fills the chip when single batches are small.
+    A process has four hardware queues and which of them new streams land on is not ours to
+    choose (the first four a process creates have shared two here, the next four had one
+    each), so fresh sets of streams are timed and every result reported."""
     w = job.w
     dev = job.ln.device
-    lanes = []
-    for _ in range(n_streams):
-        lanes.append({"stream": torch.cuda.Stream(),
-                      "ws": binding.alloc_workspace(w.B, w.T, w.V, w.beam, dev),
-                      "tok": torch.full((w.B, w.T), -1, dtype=torch.int32, device=dev),
-                      "len": torch.zeros(w.B, dtype=torch.int32, device=dev),
-                      "sc": torch.zeros(w.B, dtype=torch.float32, device=dev)})
     p = job.params(r)
-    torch.cuda.synchronize()
+    all_ms = []
+    same = True
+    for _ in range(attempts):
+        lanes = []
+        for _ in range(n_streams):
+            lanes.append({"stream": torch.cuda.Stream(),
+                          "ws": binding.alloc_workspace(w.B, w.T, w.V, w.beam, dev),
+                          "tok": torch.full((w.B, w.T), -1, dtype=torch.int32, device=dev),
+                          "len": torch.zeros(w.B, dtype=torch.int32, device=dev),
+                          "sc": torch.zeros(w.B, dtype=torch.float32, device=dev)})
+        torch.cuda.synchronize()
 
-    def round_of_calls():
-        for lane in lanes:
-            rc = binding.decode_raw(job.lp[0], job.ln, p, lane["ws"], lane["ws"].numel(),
-                                    lane["tok"], lane["len"], lane["sc"], None,
-                                    stream=lane["stream"])
-            if rc != 0:
-                raise binding.FltopError(rc, "fltop_ctc_decode")
+        def round_of_calls():
+            for lane in lanes:
+                rc = binding.decode_raw(job.lp[0], job.ln, p, lane["ws"], lane["ws"].numel(),
+                                        lane["tok"], lane["len"], lane["sc"], None,
+                                        stream=lane["stream"])
+                if rc != 0:
+                    raise binding.FltopError(rc, "fltop_ctc_decode")
 
-    for _ in range(2):
-        round_of_calls()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(reps):
-        round_of_calls()
-    torch.cuda.synchronize()
-    ms = (time.perf_counter() - t0) / reps * 1e3
-    job.decode(p)
-    torch.cuda.synchronize()
-    same = all(bool((lane["tok"] == job.tok).all().item()) for lane in lanes)
+        for _ in range(2):
+            round_of_calls()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            round_of_calls()
+        torch.cuda.synchronize()
+        all_ms.append((time.perf_counter() - t0) / reps * 1e3)
+        job.decode(p)
+        torch.cuda.synchronize()
+        same = same and all(bool((lane["tok"] == job.tok).all().item()) for lane in lanes)
+    ms = min(all_ms)
     return {"streams": n_streams, "B_each": w.B, "ms_per_round": round(ms, 4),
+            "ms_per_round_each_set_of_streams": [round(x, 4) for x in all_ms],
             "frames_per_s": round(job.frames * n_streams / (ms * 1e-3), 1),
             "streams_agree": same}
 
@@ -565,6 +573,9 @@ def main():
     }
 
     if not args.skip_extras:
+        # ---- independent batches on separate streams (first among the extras: which
+        #      hardware queue a new stream lands on depends on what the process did before)
+        result["concurrent_streams"] = concurrent_streams(torch, binding, job, r)
         # ---- pruned vs unpruned on this workload ------------------------------------
         sweep = []
         for rr in w.rel_thresholds:
@@ -606,7 +617,6 @@ def main():
             torch, binding, wide_job, 25.0)
         del wide_job
         result["batch_scaling"] = batch_scaling(torch, binding, job, r)
-        result["concurrent_streams"] = concurrent_streams(torch, binding, job, r)
         result["streaming"] = streaming_latency(torch, binding, synth, w, r, dev)
         result["paper_context"] = ("paper reports 10.5x runtime speedup and 2.78x fewer beams "
                                    "(FLToP N=4,R=0.007 vs all-32-token baseline) for a CPU "

@@ -121,6 +121,8 @@ struct BeamArgs {
     double lm_alpha, lm_beta;
     int32_t B, T, V, beam;
     int32_t lm_in_lds;  // 1: table staged into LDS
+    int32_t dcache_off;   // dynamic LDS: byte offset of the distance cache ...
+    int32_t dcache_rows;  // ... and its size in rows of one distance per thread (0: none)
     void* stream;          // streaming decode: array of StreamState<MB> (NULL for a one-shot decode)
     int32_t* out_nodes;    // streaming: [B, t_total] trie node behind each written token
     int32_t t_total;       // streaming: frames the trie and the output rows are sized for
@@ -430,9 +432,10 @@ __device__ __forceinline__ double lm_term(const FrameCtx<MB>& f, int32_t prev, i
 // Extension candidate e = i * Knb + k (entry i, non-blank survivor k): distance of its
 // score below the reference, or ~0 when it has no mass or coincides with a beam entry
 // (that entry's own update absorbs it).
-template <int LM, int MB>
-__device__ __forceinline__ uint64_t eval_ext(const FrameCtx<MB>& f, int e, int& src_entry,
-                                             int32_t& tok) {
+// Extension candidate number e names entry i = e / Knb and non-blank survivor k = e % Knb.
+template <int MB>
+__device__ __forceinline__ void cand_of(const FrameCtx<MB>& f, int e, int& entry, int32_t& tok,
+                                        double& lp) {
     // the reciprocal is rounded up, so for large e the quotient can come out one too large
     // (never more): a negative remainder says so
     int i = f.Knb > 1 ? (int)__umulhi((uint32_t)e, f.div_magic) : e;
@@ -441,8 +444,17 @@ __device__ __forceinline__ uint64_t eval_ext(const FrameCtx<MB>& f, int e, int& 
         --i;
         k += f.Knb;
     }
+    entry = i;
+    tok = surv_tok_lp(f, f.nb0 + k, lp);
+}
+
+template <int LM, int MB>
+__device__ __forceinline__ uint64_t eval_ext(const FrameCtx<MB>& f, int e, int& src_entry,
+                                             int32_t& tok) {
+    int i;
+    int32_t s;
     double lps;
-    const int32_t s = surv_tok_lp(f, f.nb0 + k, lps);
+    cand_of(f, e, i, s, lps);
     src_entry = i;
     tok = s;
     // the four reads go out together; the children list is walked only on a mask hit
@@ -650,6 +662,12 @@ void beam_kernel(BeamArgs a) {
     uint16_t* s_tok = reinterpret_cast<uint16_t*>(dyn_lds + (size_t)V * sizeof(float));
     float* lm_s = reinterpret_cast<float*>(dyn_lds + lm_lds_offset(V));
     constexpr bool has_lm = LM != kLmNone;
+    // Distances of the candidates beyond the register cache, as the first histogram pass
+    // worked them out: the later passes and the selection read them back instead of
+    // evaluating the candidate again (row j, this thread's place = its candidate number
+    // kRegCand + j).  A thread only ever reads what it wrote itself.
+    uint64_t* const dcache = reinterpret_cast<uint64_t*>(dyn_lds + a.dcache_off) + tid;
+    const int drows = a.dcache_rows;
 
     StreamState<MB>* const carried =
         a.stream ? static_cast<StreamState<MB>*>(a.stream) + b : nullptr;  // uniform
@@ -941,9 +959,20 @@ void beam_kernel(BeamArgs a) {
                     for (int m = kRegCand; m < M; ++m) {
                         const int e = e_first + m * kThreads;
                         if (e >= n_ext) break;
-                        int se;
-                        int32_t tk;
-                        const uint64_t D = eval_ext<LM>(fc, e, se, tk);
+                        int se = 0;
+                        int32_t tk = 0;
+                        uint64_t D;
+                        const int row = m - kRegCand;
+                        if (iter > 0 && row < drows) {
+                            D = dcache[row * kThreads];
+                            if (w.mode != 0 && D == w.Dfix) {  // its hash will be asked for
+                                double lp_unused;
+                                cand_of(fc, e, se, tk, lp_unused);
+                            }
+                        } else {
+                            D = eval_ext<LM>(fc, e, se, tk);
+                            if (row < drows) dcache[row * kThreads] = D;
+                        }
                         if (windowed) nearest = D < nearest ? D : nearest;
                         if (D != kAllOnes)
                             hist_add_many(fc, w, D, se, tk, hfine, hcoarse, n_clamp);
@@ -1038,9 +1067,21 @@ void beam_kernel(BeamArgs a) {
                     for (int m = kRegCand; m < M; ++m) {
                         const int e = e_first + m * kThreads;
                         if (e >= n_ext) break;
-                        int se;
-                        int32_t tk;
-                        const uint64_t D = eval_ext<LM>(fc, e, se, tk);
+                        int se = 0;
+                        int32_t tk = 0;
+                        uint64_t D;
+                        const int row = m - kRegCand;
+                        if (row < drows) {
+                            D = dcache[row * kThreads];
+                            // only a member of the boundary bucket is looked at further
+                            const bool maybe = w.mode != 0 ? D == w.Dfix
+                                                           : (D >= w.lo && window_bin(w, D) == bstar);
+                            if (!maybe) continue;
+                            double lp_unused;
+                            cand_of(fc, e, se, tk, lp_unused);
+                        } else {
+                            D = eval_ext<LM>(fc, e, se, tk);
+                        }
                         if (D != kAllOnes)
                             boundary_add(fc, w, bstar, D, se, tk, &sh_blcount, bl_D, bl_h);
                     }
@@ -1133,8 +1174,18 @@ void beam_kernel(BeamArgs a) {
             uint64_t D = kAllOnes, hh = 0;
             bool have_h = false;
             if (e < n_ext) {
-                D = eval_ext<LM>(fc, e, se, tk);
-                if (D != kAllOnes) sel = is_selected(fc, selD, selH, D, se, tk, hh, have_h);
+                const int row = m - kRegCand;
+                if (row < drows) {
+                    D = dcache[row * kThreads];
+                    if (D != kAllOnes && D <= selD) {  // a contender: now its entry and token
+                        double lp_unused;
+                        cand_of(fc, e, se, tk, lp_unused);
+                    }
+                } else {
+                    D = eval_ext<LM>(fc, e, se, tk);
+                }
+                if (D != kAllOnes && D <= selD)
+                    sel = is_selected(fc, selD, selH, D, se, tk, hh, have_h);
             }
             const uint64_t m_sel = __ballot(sel);
             if (m_sel == 0) continue;
@@ -1507,6 +1558,9 @@ hipError_t launch_beam(const int32_t* lengths, int32_t B, int32_t T, int32_t V,
     a.nbest_pnb = p.nbest_pnb;
     size_t dyn = lm_lds_offset(V);
     if (a.lm_in_lds) dyn += (size_t)V * V * sizeof(float);
+    dyn = (dyn + 15) / 16 * 16;
+    a.dcache_off = (int32_t)dyn;
+    a.dcache_rows = 0;
     // Workgroup size: frames of a small vocabulary have a few dozen candidates, and the cost of
     // a frame is its barriers and its longest wavefront, so four wavefronts are best; a large
     // vocabulary leaves hundreds to thousands of candidates per frame, which eight wavefronts
@@ -1536,6 +1590,13 @@ hipError_t launch_beam(const int32_t* lengths, int32_t B, int32_t T, int32_t V,
     // 120 M; B = 512: 93 M against 111 M)
     const bool very_dense = (int64_t)B > (int64_t)n_cu * 2;
     const bool tiny_state = p.beam <= kBeamTiny && carried == nullptr;
+    // Distance cache: a batch that leaves LDS to spare (at most two workgroups per CU) gets
+    // rows for the candidates beyond the register cache, 48 KB with 512 threads (frames of up
+    // to 7168 candidates are evaluated once), 16 KB with 256.
+    if (!dense && !large_beam) {
+        a.dcache_rows = wide ? 12 : 8;
+        dyn += (size_t)a.dcache_rows * (wide ? kThreadsLarge : kThreadsSmall) * sizeof(uint64_t);
+    }
 #define FLTOP_LAUNCH_BEAM(LM_)                                                               \
     do {                                                                                     \
         if (large_beam)                                                                      \

@@ -299,9 +299,13 @@ __device__ __forceinline__ uint64_t wave_min_u64(uint64_t v) {
     return ((uint64_t)hi << 32) | lo;
 }
 
-// dynamic LDS: dense_lp[V] fp32, s_tok[V] u16, then (optionally) the LM table
-__host__ __device__ inline size_t lm_lds_offset(int V) {
+// dynamic LDS: dense_lp[V] fp32, s_tok[V] u16, in the 512-thread builds s_lp[V] fp32, then
+// (optionally) the LM table
+__host__ __device__ inline size_t s_lp_lds_offset(int V) {
     return (((size_t)V * (sizeof(float) + sizeof(uint16_t))) + 15) / 16 * 16;
+}
+__host__ __device__ inline size_t lm_lds_offset(int V, bool with_s_lp) {
+    return s_lp_lds_offset(V) + (with_s_lp ? ((size_t)V * sizeof(float) + 15) / 16 * 16 : 0);
 }
 
 // Optional per-phase cycle accounting (thread 0 of every workgroup), compiled in only
@@ -342,6 +346,7 @@ struct FrameCtx {
     const Links<MB>* lk;
     const float* dense_lp;   // LDS, K > 6 only: log-prob by token, -inf if pruned
     const uint16_t* s_tok;   // LDS, K > 6 only: surviving tokens, ascending
+    const float* s_lp;       // LDS, K > 6 only, 512-thread builds: their log-probs, same order
     LdsFloatPtr lm_lds;      // LM table staged in LDS (kernel variant kLmLds)
     const float* lm_glb;     // LM table in global memory (kernel variant kLmGlobal)
     double lm_alpha, lm_beta;
@@ -472,6 +477,93 @@ __device__ __forceinline__ uint64_t eval_ext(const FrameCtx<MB>& f, int e, int& 
     const double sc = src + lps + lm_term<LM>(f, li, s);
     if (!(sc > -INFINITY)) return kAllOnes;
     return f.Rk - order_key(sc);
+}
+
+// ---- 512-thread builds: entry-major candidates --------------------------------------------
+// Frames of a large vocabulary (or a large beam) have thousands of candidates, dozens per
+// thread.  There a thread takes all its candidates from ONE beam entry, which it reads once
+// per frame, and "is entry i extended by token s already in the beam?" is one probe of a
+// table of (parent place, token) pairs, whatever the number of children (with lanes on
+// different entries, walking the children lists would cost every lane the longest list).
+
+// What an extension candidate needs of its beam entry.
+struct EntryView {
+    int32_t last;      // the entry's last token
+    uint32_t kidmask;  // bit (token & 31) of every child in the beam
+    double ptot, pb;   // total mass, and the mass of alignments ending in blank
+};
+
+template <int MB>
+__device__ __forceinline__ EntryView view_entry(const FrameCtx<MB>& f, int i) {
+    EntryView v;
+    v.last = f.cur->last[i];
+    v.kidmask = f.lk->kidmask[i];
+    v.ptot = f.cur->ptot[i];
+    v.pb = f.collapsed ? v.ptot : f.cur->pb[i];
+    return v;
+}
+
+__device__ __forceinline__ uint32_t kid_key(int parent, int32_t tok) {
+    return ((uint32_t)parent << 16) | ((uint32_t)tok & 0xffffu);
+}
+static_assert(FLTOP_MAX_VOCAB <= 65536 && FLTOP_MAX_BEAM <= 32768, "a (place, token) pair is 32 bits");
+constexpr uint32_t kNoKid = 0xffffffffu;
+
+// kidset: open addressing over `slots` (a power of two) words, kNoKid = empty
+__device__ __forceinline__ void kidset_insert(uint32_t* kidset, int slots, int parent, int32_t tok) {
+    const uint32_t key = kid_key(parent, tok);
+    uint32_t hs = (key * 2654435761u >> 12) & (slots - 1);
+    for (int probe = 0; probe < slots; ++probe) {
+        if (atomicCAS(&kidset[hs], kNoKid, key) == kNoKid) break;
+        hs = (hs + 1) & (slots - 1);
+    }
+}
+
+__device__ __forceinline__ bool kidset_has(const uint32_t* kidset, int slots, int parent, int32_t tok) {
+    const uint32_t key = kid_key(parent, tok);
+    uint32_t hs = (key * 2654435761u >> 12) & (slots - 1);
+    for (int probe = 0; probe < slots; ++probe) {
+        const uint32_t v = kidset[hs];
+        if (v == key) return true;
+        if (v == kNoKid) return false;
+        hs = (hs + 1) & (slots - 1);
+    }
+    return false;
+}
+
+// (token, log-prob) of survivor k, the staged ones by rank
+template <int MB>
+__device__ __forceinline__ int32_t surv_by_rank(const FrameCtx<MB>& f, int k, double& lp) {
+    if (f.big) {
+        lp = (double)f.s_lp[k];
+        return (int32_t)f.s_tok[k];
+    }
+    return surv_tok_lp(f, k, lp);
+}
+
+// Extension of entry i (seen as `v`) by non-blank survivor k: distance of its score below
+// the reference, or ~0 when it has no mass or coincides with a beam entry.
+template <int LM, int MB>
+__device__ __forceinline__ uint64_t eval_ext_of(const FrameCtx<MB>& f, const EntryView& v, int i,
+                                                int k, const uint32_t* kidset, int kid_slots,
+                                                int32_t& tok) {
+    double lps;
+    const int32_t s = surv_by_rank(f, f.nb0 + k, lps);
+    tok = s;
+    if ((v.kidmask >> (s & 31)) & 1u) {  // maybe a child i+s is in the beam
+        if (kidset_has(kidset, kid_slots, i, s)) return kAllOnes;
+    }
+    const double src = (s == v.last) ? v.pb : v.ptot;
+    const double sc = src + lps + lm_term<LM>(f, v.last, s);
+    if (!(sc > -INFINITY)) return kAllOnes;
+    return f.Rk - order_key(sc);
+}
+
+// Token of non-blank survivor k alone (for a candidate whose distance is already known).
+template <int MB>
+__device__ __forceinline__ int32_t ext_token(const FrameCtx<MB>& f, int k) {
+    double lp_unused;
+    return surv_by_rank(f, f.nb0 + k, lp_unused);
 }
 
 template <int MB>
@@ -639,6 +731,10 @@ void beam_kernel(BeamArgs a) {
     constexpr int kMaxBeam = MB;
     constexpr int kHashSlots = 4 * MB;
     static_assert(THREADS >= MB, "one thread per beam entry");
+    // the 512-thread builds take a thread's candidates from one entry (see EntryView)
+    constexpr bool kEntryMajor = THREADS == kThreadsLarge;
+    constexpr int kKidSlots = kEntryMajor ? 4 * MB : 4;
+    __shared__ uint32_t kidset2[2][kKidSlots];  // (parent place, token) pairs, per generation
     __shared__ BeamSlab<MB> slab[2];
     __shared__ Links<MB> links[2];
     __shared__ __align__(16) uint32_t hfine[kFine];
@@ -660,7 +756,8 @@ void beam_kernel(BeamArgs a) {
 
     float* dense_lp = reinterpret_cast<float*>(dyn_lds);
     uint16_t* s_tok = reinterpret_cast<uint16_t*>(dyn_lds + (size_t)V * sizeof(float));
-    float* lm_s = reinterpret_cast<float*>(dyn_lds + lm_lds_offset(V));
+    float* s_lp = reinterpret_cast<float*>(dyn_lds + s_lp_lds_offset(V));  // kEntryMajor only
+    float* lm_s = reinterpret_cast<float*>(dyn_lds + lm_lds_offset(V, kEntryMajor));
     constexpr bool has_lm = LM != kLmNone;
     // Distances of the candidates beyond the register cache, as the first histogram pass
     // worked them out: the later passes and the selection read them back instead of
@@ -709,6 +806,8 @@ void beam_kernel(BeamArgs a) {
         }
         for (int i = tid; i < kHashSlots; i += kThreads) links[g2].ht[i] = -1;
     }
+    if (kEntryMajor)
+        for (int i = tid; i < 2 * kKidSlots; i += kThreads) (&kidset2[0][0])[i] = kNoKid;
     if (tid == 0) {
         sh_nnew = 0;
         sh_blcount = 0;
@@ -744,16 +843,24 @@ void beam_kernel(BeamArgs a) {
         lm_ub = fmax(0.0, (double)part);
     }
     __syncthreads();
+    if (kEntryMajor && carried) {  // the pair table is not carried: rebuild it from the links
+        if (tid < carried->n_live && links[0].par[tid] >= 0)
+            kidset_insert(kidset2[0], kKidSlots, links[0].par[tid], slab[0].last[tid]);
+        __syncthreads();
+    }
 
     FrameCtx<MB> fc;
     fc.dense_lp = dense_lp;
     fc.s_tok = s_tok;
+    fc.s_lp = s_lp;
     fc.lm_lds = (LdsFloatPtr)lm_s;
     fc.lm_glb = a.lm_table;
     fc.lm_alpha = a.lm_alpha;
     fc.lm_beta = a.lm_beta;
     fc.V = V;
 
+    int mapped_for = -1;  // kEntryMajor: the beam size the thread -> entry mapping was made for
+    int ext_i = 0, ext_g = 0, ext_G = 1;
     int gen = 0;         // beam generation: slab[gen], links[gen]
     int n_live = 1;
     double bias = 0.0;       // log-mass of the blank-only frames, common to every entry
@@ -869,6 +976,7 @@ void beam_kernel(BeamArgs a) {
             for (int k = tid; k < K; k += kThreads) {
                 const Survivor s = (k < kRegK) ? full->first[k] : recs[k];
                 s_tok[k] = (uint16_t)s.tok;
+                if (kEntryMajor) s_lp[k] = s.lp;
                 dense_lp[s.tok] = s.lp;
             }
         }
@@ -879,10 +987,55 @@ void beam_kernel(BeamArgs a) {
         fc.Knb = K - fc.nb0;
         fc.div_magic = hd.div_magic;
         const double lp_blank = fc.nb0 ? (double)hd.first[0].lp : -INFINITY;
+        // Extension candidate e = i * Knb + k is entry i extended by non-blank survivor k.
+        // Thread numbers are taken from the upper half of the wavefronts first (the lower
+        // half has the stays).  Plain builds: a thread takes e = e_first, e_first + kThreads, ...
+        // Entry-major builds: entry i is shared by G = kThreads / n_live threads, of which
+        // number g takes k = g, g + G, g + 2G, ...
         const int n_ext = n_live * fc.Knb;
-        const int M = (n_ext + kThreads - 1) / kThreads;  // extension candidates per thread
-        // the upper half of the wavefronts takes them first (the lower half has the stays)
         const int e_first = (tid + kThreads / 2) & (kThreads - 1);
+        if (kEntryMajor && n_live != mapped_for) {  // uniform; the beam is full most of the time
+            ext_g = e_first / n_live;
+            ext_i = e_first - ext_g * n_live;
+            ext_G = kThreads / n_live;
+            mapped_for = n_live;
+        }
+        const int G = ext_G;
+        const bool ext_thread = ext_g < G && ext_g < fc.Knb;  // kEntryMajor only
+        const int M = kEntryMajor ? (fc.Knb + G - 1) / G  // most candidates any thread has
+                                  : (n_ext + kThreads - 1) / kThreads;
+        const uint32_t* const kids = kidset2[gen];
+        EntryView ev;
+        ev.last = -1;
+        ev.kidmask = 0u;
+        ev.ptot = ev.pb = -INFINITY;
+        // candidate number m of this thread: does it exist, and what names it
+        auto cand_at = [&](int m, int& e, int& k) -> bool {
+            if (kEntryMajor) {
+                k = ext_g + G * m;
+                e = 0;
+                return ext_thread && k < fc.Knb;
+            }
+            e = e_first + m * kThreads;
+            k = 0;
+            return e < n_ext;
+        };
+        auto cand_eval = [&](int e, int k, int& se, int32_t& tk) -> uint64_t {
+            if (kEntryMajor) {
+                se = ext_i;
+                return eval_ext_of<LM>(fc, ev, ext_i, k, kids, kKidSlots, tk);
+            }
+            return eval_ext<LM>(fc, e, se, tk);
+        };
+        auto cand_name = [&](int e, int k, int& se, int32_t& tk) {  // without evaluating it
+            if (kEntryMajor) {
+                se = ext_i;
+                tk = ext_token(fc, k);
+            } else {
+                double lp_unused;
+                cand_of(fc, e, se, tk, lp_unused);
+            }
+        };
 
         // upper bound of every candidate score -> reference key
         const double ref = kmax_v + (double)hd.top + lm_ub + 1.0986122886681098 + 1e-3;
@@ -894,8 +1047,16 @@ void beam_kernel(BeamArgs a) {
         uint64_t cD0 = kAllOnes, cD1 = kAllOnes;  // ~0 marks "no live candidate"
         int cI0 = 0, cI1 = 0;
         int32_t cT0 = 0, cT1 = 0;
-        if (e_first < n_ext) cD0 = eval_ext<LM>(fc, e_first, cI0, cT0);
-        if (e_first + kThreads < n_ext) cD1 = eval_ext<LM>(fc, e_first + kThreads, cI1, cT1);
+        if (kEntryMajor) {
+            if (ext_thread) {
+                ev = view_entry(fc, ext_i);
+                cD0 = cand_eval(0, ext_g, cI0, cT0);
+                if (ext_g + G < fc.Knb) cD1 = cand_eval(0, ext_g + G, cI1, cT1);
+            }
+        } else {
+            if (e_first < n_ext) cD0 = eval_ext<LM>(fc, e_first, cI0, cT0);
+            if (e_first + kThreads < n_ext) cD1 = eval_ext<LM>(fc, e_first + kThreads, cI1, cT1);
+        }
         PHASE_MARK(8);
         // ... and the stay candidate of entry `tid`
         double my_pb = -INFINITY, my_pnb = -INFINITY, my_tot = -INFINITY;
@@ -957,20 +1118,17 @@ void beam_kernel(BeamArgs a) {
                 if (M > kRegCand) {
                     int n_clamp = 0;
                     for (int m = kRegCand; m < M; ++m) {
-                        const int e = e_first + m * kThreads;
-                        if (e >= n_ext) break;
+                        int e, k;
+                        if (!cand_at(m, e, k)) break;
                         int se = 0;
                         int32_t tk = 0;
                         uint64_t D;
                         const int row = m - kRegCand;
                         if (iter > 0 && row < drows) {
                             D = dcache[row * kThreads];
-                            if (w.mode != 0 && D == w.Dfix) {  // its hash will be asked for
-                                double lp_unused;
-                                cand_of(fc, e, se, tk, lp_unused);
-                            }
+                            if (w.mode != 0 && D == w.Dfix) cand_name(e, k, se, tk);  // for its hash
                         } else {
-                            D = eval_ext<LM>(fc, e, se, tk);
+                            D = cand_eval(e, k, se, tk);
                             if (row < drows) dcache[row * kThreads] = D;
                         }
                         if (windowed) nearest = D < nearest ? D : nearest;
@@ -1065,8 +1223,8 @@ void beam_kernel(BeamArgs a) {
                     if (cD1 != kAllOnes)
                         boundary_add(fc, w, bstar, cD1, cI1, cT1, &sh_blcount, bl_D, bl_h);
                     for (int m = kRegCand; m < M; ++m) {
-                        const int e = e_first + m * kThreads;
-                        if (e >= n_ext) break;
+                        int e, k;
+                        if (!cand_at(m, e, k)) break;
                         int se = 0;
                         int32_t tk = 0;
                         uint64_t D;
@@ -1077,10 +1235,9 @@ void beam_kernel(BeamArgs a) {
                             const bool maybe = w.mode != 0 ? D == w.Dfix
                                                            : (D >= w.lo && window_bin(w, D) == bstar);
                             if (!maybe) continue;
-                            double lp_unused;
-                            cand_of(fc, e, se, tk, lp_unused);
+                            cand_name(e, k, se, tk);
                         } else {
-                            D = eval_ext<LM>(fc, e, se, tk);
+                            D = cand_eval(e, k, se, tk);
                         }
                         if (D != kAllOnes)
                             boundary_add(fc, w, bstar, D, se, tk, &sh_blcount, bl_D, bl_h);
@@ -1167,22 +1324,20 @@ void beam_kernel(BeamArgs a) {
                          trie_stride);
         }
         for (int m = kRegCand; m < M; ++m) {  // candidates beyond the register cache
-            const int e = e_first + m * kThreads;
+            int e, k;
+            const bool there = cand_at(m, e, k);
             bool sel = false;
             int se = 0;
             int32_t tk = 0;
             uint64_t D = kAllOnes, hh = 0;
             bool have_h = false;
-            if (e < n_ext) {
+            if (there) {
                 const int row = m - kRegCand;
                 if (row < drows) {
                     D = dcache[row * kThreads];
-                    if (D != kAllOnes && D <= selD) {  // a contender: now its entry and token
-                        double lp_unused;
-                        cand_of(fc, e, se, tk, lp_unused);
-                    }
+                    if (D != kAllOnes && D <= selD) cand_name(e, k, se, tk);  // a contender
                 } else {
-                    D = eval_ext<LM>(fc, e, se, tk);
+                    D = cand_eval(e, k, se, tk);
                 }
                 if (D != kAllOnes && D <= selD)
                     sel = is_selected(fc, selD, selH, D, se, tk, hh, have_h);
@@ -1226,7 +1381,10 @@ void beam_kernel(BeamArgs a) {
             }
             lkn->par[tid] = p;
             if (p >= 0) {
-                lkn->next_kid[tid] = atomicExch(&lkn->first_kid[p], tid);
+                if (kEntryMajor)
+                    kidset_insert(kidset2[gen ^ 1], kKidSlots, p, nxt->last[tid]);
+                else
+                    lkn->next_kid[tid] = atomicExch(&lkn->first_kid[p], tid);
                 atomicOr(&lkn->kidmask[p], 1u << (nxt->last[tid] & 31));
             }
         }
@@ -1240,6 +1398,9 @@ void beam_kernel(BeamArgs a) {
             const int4 ones = make_int4(-1, -1, -1, -1), zeros = make_int4(0, 0, 0, 0);
             for (int i = u; i < kHashSlots / 4; i += kThreads / 2)
                 reinterpret_cast<int4*>(lk->ht)[i] = ones;
+            if (kEntryMajor)
+                for (int i = u; i < kKidSlots / 4; i += kThreads / 2)
+                    reinterpret_cast<int4*>(kidset2[gen])[i] = ones;
             for (int i = u; i < kMaxBeam / 4; i += kThreads / 2) {
                 reinterpret_cast<int4*>(lk->first_kid)[i] = ones;
                 reinterpret_cast<int4*>(lk->kidmask)[i] = zeros;
@@ -1556,7 +1717,15 @@ hipError_t launch_beam(const int32_t* lengths, int32_t B, int32_t T, int32_t V,
     a.nbest_lengths = p.nbest_lengths;
     a.nbest_pb = p.nbest_pb;
     a.nbest_pnb = p.nbest_pnb;
-    size_t dyn = lm_lds_offset(V);
+    const bool wide = V > 64;
+    const bool large_beam = p.beam > kBeamSmall;
+    int n_cu = 0;
+    hipError_t qe = compute_units(&n_cu);
+    if (qe != hipSuccess) return qe;
+    const bool dense = (int64_t)B > (int64_t)n_cu * (wide ? 1 : 2);
+    const bool very_dense = (int64_t)B > (int64_t)n_cu * 2;
+    const bool threads_512 = large_beam || (wide && !very_dense);  // as dispatched below
+    size_t dyn = lm_lds_offset(V, threads_512);
     if (a.lm_in_lds) dyn += (size_t)V * V * sizeof(float);
     dyn = (dyn + 15) / 16 * 16;
     a.dcache_off = (int32_t)dyn;
@@ -1579,16 +1748,9 @@ hipError_t launch_beam(const int32_t* lengths, int32_t B, int32_t T, int32_t V,
     // cut for four wavefronts per SIMD, 564 M with two wavefronts per utterance, 679 M with
     // the small state as well.  A streaming decode keeps the 128-entry state throughout (its
     // carried records are laid out for it).
-    const bool wide = V > 64;
-    const bool large_beam = p.beam > kBeamSmall;
-    int n_cu = 0;
-    hipError_t qe = compute_units(&n_cu);
-    if (qe != hipSuccess) return qe;
-    const bool dense = (int64_t)B > (int64_t)n_cu * (wide ? 1 : 2);
-    // large vocabulary: eight wavefronts per utterance while the whole batch is resident that
-    // way (two workgroups per CU), four beyond (B = 1024, V = 1024: 143 M frames/s against
+    // (large vocabulary: eight wavefronts per utterance while the whole batch is resident that
+    // way, two workgroups per CU, four beyond: B = 1024, V = 1024: 143 M frames/s against
     // 120 M; B = 512: 93 M against 111 M)
-    const bool very_dense = (int64_t)B > (int64_t)n_cu * 2;
     const bool tiny_state = p.beam <= kBeamTiny && carried == nullptr;
     // Distance cache: a batch that leaves LDS to spare (at most two workgroups per CU) gets
     // rows for the candidates beyond the register cache, 48 KB with 512 threads (frames of up

@@ -35,6 +35,12 @@
 //  - "stay" candidates (which need the log-sum-exps) and extension candidates are
 //    mapped to different wavefronts so that they are evaluated side by side, and
 //    the end-of-frame clean-up is done by the wavefronts that have no links to set.
+//
+// The kernel is built several times over (workgroup size, beam capacity, register budget):
+// four wavefronts for the frames of a pruned small vocabulary, eight with an entry-major
+// candidate mapping where frames hold hundreds to thousands of candidates, and two with a
+// tighter register budget for batches that fill the chip, where instruction issue and
+// residency count instead of one frame's latency (see launch_beam).
 #include "fltop_internal.h"
 
 namespace fltop {

@@ -181,3 +181,28 @@ def test_stream_entry_points_validate_before_any_launch(lib):
     q.rel_threshold = 0.5
     q.top_n = -1
     assert call(params=q) == -9
+
+
+def test_header_is_plain_c_and_the_struct_layout_matches_the_binding(tmp_path):
+    """The boundary is a C ABI: the header must compile as C99, and the ctypes mirror of
+    fltop_params / fltop_stats must have the C compiler's sizes and field offsets."""
+    import subprocess
+    fields = [name for name, _ in binding.FltopParams._fields_]
+    prog = ['#include <stddef.h>', '#include <stdio.h>', '#include "fltop_ctc.h"',
+            'int main(void) {', '  printf("%zu %zu\\n", sizeof(fltop_params), sizeof(fltop_stats));']
+    for name in fields:
+        prog.append(f'  printf("{name} %zu\\n", offsetof(fltop_params, {name}));')
+    prog += ['  return 0;', '}']
+    src = tmp_path / "abi_probe.c"
+    src.write_text("\n".join(prog) + "\n")
+    exe = tmp_path / "abi_probe"
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I",
+                    os.path.join(ROOT, "include"), str(src), "-o", str(exe)], check=True)
+    out = subprocess.run([str(exe)], capture_output=True, text=True, check=True).stdout.split("\n")
+    size_params, size_stats = (int(x) for x in out[0].split())
+    assert size_params == ctypes.sizeof(binding.FltopParams)
+    assert size_stats == 8 * len(binding.STATS_FIELDS)
+    for line in out[1:]:
+        if line:
+            name, off = line.split()
+            assert getattr(binding.FltopParams, name).offset == int(off), name

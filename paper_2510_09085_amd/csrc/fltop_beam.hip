@@ -1748,7 +1748,7 @@ hipError_t launch_beam(const int32_t* lengths, int32_t B, int32_t T, int32_t V,
     // (two per SIMD) evaluate twice as fast (measured: V = 1024 27% faster per decode with 512
     // threads, V = 32 at r = 0.01 6% slower).
     // Beam capacity: up to 128 entries the beam state takes 30 KB of LDS; beyond, the
-    // 512-entry build (100 KB, one thread per entry, one workgroup per CU) is used.
+    // 512-entry build (116 KB, one thread per entry, one workgroup per CU) is used.
     // Residency: at two wavefronts per SIMD a CU holds two 256-thread workgroups (one of 512
     // threads).  A batch with more utterances than that over the whole chip is bound by
     // instruction issue, not by one frame's latency, and small frames then run best as two

@@ -61,7 +61,7 @@ constexpr int kCoarse = 64;  // one per lane; a coarse bin covers 16 fine bins
 constexpr int kExactCap = 64;
 constexpr int kMaxShift = 54;  // kFine << kMaxShift covers all 64-bit distances
 constexpr int kRegK = kInlineSurvivors;  // survivors kept in registers
-constexpr int kRegCand = 2;              // extension candidates cached per thread
+constexpr int kRegCand = 1;              // extension candidates kept in registers per thread
 constexpr int kChunk = 32;               // frame headers staged per chunk
 constexpr int kWaypoints = 256;
 constexpr uint64_t kGolden = 0x9E3779B97F4A7C15ull;
@@ -1049,19 +1049,18 @@ void beam_kernel(BeamArgs a) {
         const uint64_t Rk = fc.Rk;
 
         // ---- candidates owned by this thread ----------------------------------------
-        // two cached extension candidates (e_first, e_first + 256) ...
-        uint64_t cD0 = kAllOnes, cD1 = kAllOnes;  // ~0 marks "no live candidate"
-        int cI0 = 0, cI1 = 0;
-        int32_t cT0 = 0, cT1 = 0;
+        // the first extension candidate stays in registers (the others, if any, are worked
+        // on one after the other and leave their distances in LDS) ...
+        uint64_t cD0 = kAllOnes;  // ~0 marks "no live candidate"
+        int cI0 = 0;
+        int32_t cT0 = 0;
         if (kEntryMajor) {
             if (ext_thread) {
                 ev = view_entry(fc, ext_i);
                 cD0 = cand_eval(0, ext_g, cI0, cT0);
-                if (ext_g + G < fc.Knb) cD1 = cand_eval(0, ext_g + G, cI1, cT1);
             }
         } else {
             if (e_first < n_ext) cD0 = eval_ext<LM>(fc, e_first, cI0, cT0);
-            if (e_first + kThreads < n_ext) cD1 = eval_ext<LM>(fc, e_first + kThreads, cI1, cT1);
         }
         PHASE_MARK(8);
         // ... and the stay candidate of entry `tid`
@@ -1115,11 +1114,9 @@ void beam_kernel(BeamArgs a) {
                 }
                 if (D_stay != kAllOnes) hist_add(fc, w, D_stay, tid, -1, hfine, hcoarse);
                 if (cD0 != kAllOnes) hist_add(fc, w, cD0, cI0, cT0, hfine, hcoarse);
-                if (cD1 != kAllOnes) hist_add(fc, w, cD1, cI1, cT1, hfine, hcoarse);
                 uint64_t nearest = kAllOnes;  // this thread's best candidate (score window only)
                 if (windowed) {
                     nearest = D_stay < cD0 ? D_stay : cD0;
-                    nearest = cD1 < nearest ? cD1 : nearest;
                 }
                 if (M > kRegCand) {
                     int n_clamp = 0;
@@ -1226,8 +1223,6 @@ void beam_kernel(BeamArgs a) {
                         boundary_add(fc, w, bstar, D_stay, tid, -1, &sh_blcount, bl_D, bl_h);
                     if (cD0 != kAllOnes)
                         boundary_add(fc, w, bstar, cD0, cI0, cT0, &sh_blcount, bl_D, bl_h);
-                    if (cD1 != kAllOnes)
-                        boundary_add(fc, w, bstar, cD1, cI1, cT1, &sh_blcount, bl_D, bl_h);
                     for (int m = kRegCand; m < M; ++m) {
                         int e, k;
                         if (!cand_at(m, e, k)) break;
@@ -1302,16 +1297,14 @@ void beam_kernel(BeamArgs a) {
 
         // ---- compaction: selected candidates become the next beam ------------------
         {
-            // the stay candidate and the cached extensions share one slot allocation per wave
-            uint64_t hh0 = 0, hh1 = 0, hhs = 0;
-            bool hv0 = false, hv1 = false, hvs = false;
+            // the stay candidate and the first extension share one slot allocation per wave
+            uint64_t hh0 = 0, hhs = 0;
+            bool hv0 = false, hvs = false;
             const bool sel_s =
                 D_stay != kAllOnes && is_selected(fc, selD, selH, D_stay, tid, -1, hhs, hvs);
             const bool sel_0 =
                 cD0 != kAllOnes && is_selected(fc, selD, selH, cD0, cI0, cT0, hh0, hv0);
-            const bool sel_1 =
-                cD1 != kAllOnes && is_selected(fc, selD, selH, cD1, cI1, cT1, hh1, hv1);
-            const int cnt = (sel_s ? 1 : 0) + (sel_0 ? 1 : 0) + (sel_1 ? 1 : 0);
+            const int cnt = (sel_s ? 1 : 0) + (sel_0 ? 1 : 0);
             const int incl = wave_inclusive_scan(cnt);
             const int wave_total = __builtin_amdgcn_readlane(incl, kWave - 1);
             int base = 0;
@@ -1324,9 +1317,6 @@ void beam_kernel(BeamArgs a) {
             if (sel_s) emit_stay(fc, nxt, lkn, newslot, slot++, beam, tid, my_pb, my_pnb, my_tot);
             if (sel_0)
                 emit_ext(fc, nxt, lkn, slot++, beam, t_base + t, cD0, cI0, cT0, hh0, hv0, trie,
-                         trie_stride);
-            if (sel_1)
-                emit_ext(fc, nxt, lkn, slot++, beam, t_base + t, cD1, cI1, cT1, hh1, hv1, trie,
                          trie_stride);
         }
         for (int m = kRegCand; m < M; ++m) {  // candidates beyond the register cache
@@ -1764,12 +1754,15 @@ hipError_t launch_beam(const int32_t* lengths, int32_t B, int32_t T, int32_t V,
     // way, two workgroups per CU, four beyond: B = 1024, V = 1024: 143 M frames/s against
     // 120 M; B = 512: 93 M against 111 M)
     const bool tiny_state = p.beam <= kBeamTiny && carried == nullptr;
-    // Distance cache: a batch that leaves LDS to spare (at most two workgroups per CU) gets
-    // rows for the candidates beyond the register cache, 48 KB with 512 threads (frames of up
-    // to 7168 candidates are evaluated once), 16 KB with 256.
-    if (!dense && !large_beam) {
-        a.dcache_rows = wide ? 12 : 8;
-        dyn += (size_t)a.dcache_rows * (wide ? kThreadsLarge : kThreadsSmall) * sizeof(uint64_t);
+    // Distance cache: rows for the candidates beyond the one a thread keeps in registers.  A
+    // batch that leaves LDS to spare (at most two workgroups per CU) gets 48 KB with 512
+    // threads (frames of up to 6656 candidates are evaluated once) or 16 KB with 256; the
+    // builds for large batches get one row (1-4 KB: up to two candidates per thread).
+    if (!large_beam) {
+        const int threads = threads_512 ? kThreadsLarge
+                                        : (wide || !dense ? kThreadsSmall : kThreadsDense);
+        a.dcache_rows = dense ? 1 : (wide ? 12 : 8);
+        dyn += (size_t)a.dcache_rows * threads * sizeof(uint64_t);
     }
 #define FLTOP_LAUNCH_BEAM(LM_)                                                               \
     do {                                                                                     \

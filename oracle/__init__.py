@@ -13,7 +13,9 @@ from typing import Optional
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libfltop_oracle.so")
+# FLTOP_ORACLE_LIB names another build of the oracle (the mutation test points it at oracles
+# with a planted mistake to show that the pins notice)
+LIB_PATH = os.environ.get("FLTOP_ORACLE_LIB") or os.path.join(_HERE, "libfltop_oracle.so")
 FLTOP = 0
 TEXTBOOK = 1
 

@@ -167,6 +167,35 @@ def test_hand_worked_score_window_example(oracle_lib):
             assert math.exp(got[toks]) == pytest.approx(mass, rel=1e-6)
 
 
+def test_candidate_exactly_on_the_window_floor_is_kept(oracle_lib):
+    """tests/golden/beam_window_floor_tie.txt: scores that are exact multiples of fp32(ln 2),
+    window = that same number, so two candidates sit on the floor bit for bit."""
+    L = float(np.float32(math.log(2.0)))
+    assert L == 0.693147182464599609375
+    expected = {}
+    with open(os.path.join(GOLDEN, "beam_window_floor_tie.txt")) as fh:
+        for line in fh:
+            if line.startswith("#") or not line.strip():
+                continue
+            T, prefix, mass = line.split()
+            toks = () if prefix == "-" else tuple(int(x) for x in prefix.split(","))
+            expected.setdefault(int(T), {})[toks] = float(mass)
+    assert sorted(expected) == [1, 2]
+    for T, table in expected.items():
+        lp = np.tile(np.array([-L, -2 * L, -2 * L], dtype=np.float32), (T, 1))
+        assert float(lp[0, 1]) == -2 * L  # exact in fp32
+        entries = oracle_lib.decode_beam(lp, 100, 0.0, beam_threshold=L, max_entries=100)
+        got = {tok: logsumexp([pb, pnb]) for tok, pb, pnb in entries}
+        assert set(got) == set(table), (T, got)
+        for toks, mass in table.items():
+            assert math.exp(got[toks]) == pytest.approx(mass, rel=1e-6)
+    # the tie is real: at T = 1 the two kept candidates score exactly best - window
+    one = oracle_lib.decode_beam(np.array([[-L, -2 * L, -2 * L]], dtype=np.float32), 100, 0.0,
+                                 beam_threshold=L, max_entries=100)
+    totals = sorted(logsumexp([pb, pnb]) for _, pb, pnb in one)
+    assert totals == [-2 * L, -2 * L, -L] and totals[2] - L == totals[0]
+
+
 def test_huge_window_is_no_window(oracle_lib):
     w = synth.WORKLOADS["cfg2_batch64"]
     lp, ln = synth.make_emissions(w, utterances=range(3))

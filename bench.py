@@ -4,7 +4,20 @@
 A "step" is one call of fltop_ctc_decode (prune stage + beam search + best prefix) over
 one batch of seeded synthetic emissions that already sit in HBM.  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2_batch64] [--rel-threshold 0.01]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3_varlen256] [--rel-threshold 0.01]
+
+The headline workload is the largest of the five named ones (256 utterances of 250..1500
+frames, beam 100: one workgroup per compute unit); `per_config` in the same line times every
+named workload at every threshold it lists, GPU and CPU oracle side by side.
+
+Two helper modes serve the profiles kept under profiles/:
+  python bench.py --counter-probe prune|search [--workload W]   a short fixed launch sequence to
+                                                                put under `rocprofv3 --pmc ...`
+  python bench.py --phase-clocks [--workload W]                 cycles per phase of the search stage
+                                                                (profiling build of the library)
+  python bench.py --summarise kernels  RESULTS.db [N]           rocprofv3's output database ->
+  python bench.py --summarise counters RESULTS.db [SUBSTR]      the short text tables kept there
+  python bench.py --summarise traffic  FETCH.db WRITE.db PROBE.json KERNEL_SUBSTR OUT.json
 """
 from __future__ import annotations
 
@@ -20,6 +33,8 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
 FP64_VECTOR_TFLOPS = 78.6    # MI355X fp64 vector peak (256 CUs x 4 SIMD x 16 lanes x 2 x 2.4 GHz)
+CU_COUNT = 256
+CLOCK_GHZ = 2.4              # peak engine clock
 FLOP_PER_CANDIDATE = 50.0    # 1 exp + 1 log1p (20 flop each) + 10 adds/compares, fp64
 CAND_RECORD_BYTES = 24       # score 8 B + prefix hash 8 B + (source entry, token) 8 B
 
@@ -29,7 +44,7 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="cfg2_batch64")
+    ap.add_argument("--workload", default="cfg3_varlen256")
     ap.add_argument("--rel-threshold", type=float, default=0.01)
     ap.add_argument("--skip-cpu-baseline", action="store_true")
     ap.add_argument("--skip-extras", action="store_true",
@@ -38,10 +53,33 @@ def parse_args():
                     help="run only that stage a few times (plus, for prune, a plain device copy "
                          "of known size for calibration): the program to put under "
                          "`rocprofv3 --pmc ...`")
+    ap.add_argument("--phase-clocks", action="store_true",
+                    help="per-phase cycle table of the search stage; needs the profiling build of "
+                         "the library (python -m paper_2510_09085_amd.build --define "
+                         "FLTOP_PHASE_CLOCKS --out X.so, then FLTOP_CTC_LIB=X.so)")
+    ap.add_argument("--summarise", nargs="+", metavar="ARG", default=None,
+                    help="kernels DB [N] | counters DB [SUBSTR] | traffic FETCH.db WRITE.db "
+                         "PROBE.json KERNEL_SUBSTR OUT.json: summarise rocprofv3 databases (no GPU)")
     ap.add_argument("--probe-replicas", type=int, default=1,
                     help="with --counter-probe search: decode the workload's utterances this "
                          "many times over in one batch (large-batch regime)")
     return ap.parse_args()
+
+
+def progress(msg):
+    """One line on stderr per phase: a long run shows that it is alive."""
+    print(f"[bench {time.strftime('%H:%M:%S')}] {msg}", file=sys.stderr, flush=True)
+
+
+_HOST_INPUTS = {}
+
+
+def host_inputs(synth, w):
+    """Seeded emissions and lengths of a workload on the host, drawn once per process."""
+    key = (w.name, w.B, w.T, w.V, w.seed)
+    if key not in _HOST_INPUTS:
+        _HOST_INPUTS[key] = synth.make_emissions(w)
+    return _HOST_INPUTS[key]
 
 
 class Job:
@@ -49,7 +87,7 @@ class Job:
 
     def __init__(self, torch, binding, synth, w, dev, copies=1):
         self.torch, self.binding, self.w = torch, binding, w
-        lp, ln = synth.make_emissions(w)
+        lp, ln = host_inputs(synth, w)
         self.lp_host, self.ln_host = lp, ln
         self.frames = int(ln.sum())
         self.lm_host = synth.make_bigram_lm(w.V) if w.use_lm else None
@@ -62,7 +100,7 @@ class Job:
         self.tok = torch.full((w.B, w.T), -1, dtype=torch.int32, device=dev)
         self.olen = torch.zeros(w.B, dtype=torch.int32, device=dev)
         self.sc = torch.zeros(w.B, dtype=torch.float32, device=dev)
-        self.stats = torch.zeros(len(binding.STATS_FIELDS), dtype=torch.int64, device=dev)
+        self.stats = torch.zeros(binding.STATS_WORDS, dtype=torch.int64, device=dev)
 
     def params(self, r, top_n=0, beam_threshold=0.0):
         p = self.binding.FltopParams()
@@ -327,7 +365,7 @@ def streaming_latency(torch, binding, synth, w, r, dev, chunk_frames=25, batches
     """Chunked decode with carried beam state (the paper's real-time motivation, Sec. 1):
     the workload's utterances arrive `chunk_frames` frames at a time (0.5 s of audio at 50
     frames/s); per-call latency of one chunk, and the whole utterances against one call."""
-    lp_host, ln_host = synth.make_emissions(w)
+    lp_host, ln_host = host_inputs(synth, w)
     lm = torch.from_numpy(synth.make_bigram_lm(w.V)).to(dev) if w.use_lm else None
     out = []
     for nb in batches:
@@ -378,57 +416,178 @@ def streaming_latency(torch, binding, synth, w, r, dev, chunk_frames=25, batches
     return out
 
 
-def other_workloads(torch, binding, synth, dev, skip):
-    """Whole-decode time of the remaining named workloads at their first threshold."""
+def _oracle_kwargs(w, lm):
+    return dict(lm_table=lm, lm_weight=w.lm_weight, insertion_bonus=w.insertion_bonus)
+
+
+def oracle_rate(oracle, w, lp, ln, lm, r, threads, budget_s):
+    """frames/s of the CPU oracle on a bounded sample of the workload: a short pilot (one
+    utterance, 100 frames, one thread) sizes the sample to about `budget_s` seconds; whole
+    utterances from the start of the batch when enough of them fit, otherwise `threads`
+    utterances cut to their first frames (the oracle never reads beyond a length)."""
+    import numpy as np
+    kw = _oracle_kwargs(w, lm)
+    # two pilot decodes of one utterance: the difference is the cost of frames 25..100, when the
+    # beam has filled (the first frames of an utterance are much cheaper)
+    took = []
+    for pilot in (int(min(25, ln[0])), int(min(100, ln[0]))):
+        t0 = time.perf_counter()
+        oracle.decode(lp[:1], np.array([pilot], dtype=np.int32), w.beam, r, n_threads=1, **kw)
+        took.append((pilot, time.perf_counter() - t0))
+    (f1, t1), (f2, t2) = took
+    per_thread = (f2 - f1) / max(1e-6, t2 - t1) if f2 > f1 else f1 / max(1e-6, t1)
+    want = per_thread * threads * budget_s
+    total = int(ln.sum())
+    if want >= total:
+        sel, cut, what = slice(0, w.B), ln, "whole batch"
+    else:
+        n = int(want // max(1.0, float(ln.mean())))
+        if n >= threads:
+            n = min(w.B, n)
+            sel, cut, what = slice(0, n), ln[:n], f"first {n} utterances"
+        else:
+            n = min(w.B, threads)
+            frames = int(max(25, want // n))
+            cut = np.minimum(ln[:n], frames).astype(np.int32)
+            sel, what = slice(0, n), f"first {frames} frames of the first {n} utterances"
+    t0 = time.perf_counter()
+    oracle.decode(lp[sel], np.ascontiguousarray(cut), w.beam, r, n_threads=threads, **kw)
+    dt = time.perf_counter() - t0
+    return {"frames_per_s": round(int(cut.sum()) / dt, 1), "threads": threads,
+            "sample": what, "sample_frames": int(cut.sum()), "seconds": round(dt, 2)}
+
+
+def host_threads():
+    return max(1, min(16, os.cpu_count() or 1))
+
+
+def cpu_baseline(synth, w, r, budget_s=10.0):
+    """The oracle as it stands, on the host's cores, on the headline workload."""
+    import oracle
+    threads = host_threads()
+    lp, ln = host_inputs(synth, w)
+    lm = synth.make_bigram_lm(w.V) if w.use_lm else None
+    allc = oracle_rate(oracle, w, lp, ln, lm, r, threads, budget_s)
+    one = oracle_rate(oracle, w, lp, ln, lm, r, 1, budget_s / 3)
+    unpruned = oracle_rate(oracle, w, lp, ln, lm, 0.0, threads, budget_s / 2)
+    return {"value": allc["frames_per_s"], "unit": "frames/s", "cores": threads, "kind": "oracle",
+            "sample": f"{w.name} at r={r}: {allc['sample']} ({allc['sample_frames']} frames, "
+                      f"{allc['seconds']} s) on {threads} threads; one thread: {one['sample']}; "
+                      f"unpruned (r=0): {unpruned['sample']}",
+            "one_thread_frames_per_s": one["frames_per_s"],
+            "unpruned_frames_per_s": unpruned["frames_per_s"],
+            "pruned_vs_unpruned_speedup": round(allc["frames_per_s"] / unpruned["frames_per_s"], 2)}
+
+
+def full_path_frames(torch, binding, job, r):
+    """Per utterance, the frames that are not blank-only (those run the whole frame pipeline of
+    the search stage; a run of blank-only frames costs a few additions), from the survivor
+    lists the prune stage has written."""
+    w = job.w
+    job.prune(r)
+    counts, tokens, _, _ = binding.unpack_survivors(job.ws, job.ln, w.B, w.T, w.V, w.beam)
+    blank_only = (counts == 1) & (tokens[:, 0] == 0)
+    full = ((counts > 0) & ~blank_only).reshape(w.B, w.T).sum(dim=1)
+    torch.cuda.synchronize()
+    return full.cpu().numpy()
+
+
+def search_roofline(torch, binding, job, r, st, search_avg_ms):
+    """The search stage against the fp64 vector peak of the compute units it can occupy (one
+    workgroup per utterance).  It is a serial chain of frames, so the fraction is small by
+    construction; the telling figure is the time per full-path frame."""
+    w = job.w
+    flops = FLOP_PER_CANDIDATE * st["sum_candidates"]
+    tflops = flops / (search_avg_ms * 1e-3) / 1e12
+    active = min(w.B, CU_COUNT)
+    full = full_path_frames(torch, binding, job, r)
+    longest = int(full.max()) if len(full) else 0
+    return {"kernel": "beam_kernel (search stage)", "bound": "alu",
+            "achieved": round(tflops, 6), "peak": FP64_VECTOR_TFLOPS, "unit": "TFLOP/s",
+            "frac": round(tflops / FP64_VECTOR_TFLOPS, 8),
+            "traffic": recorded_traffic("beam_kernel", w.name),
+            "avg_launch_us": round(search_avg_ms * 1e3, 2),
+            "algorithmic_flop": flops,
+            "active_cus": active,
+            "peak_on_active_cus": round(FP64_VECTOR_TFLOPS * active / CU_COUNT, 3),
+            "frac_of_active_cus": round(tflops / (FP64_VECTOR_TFLOPS * active / CU_COUNT), 8),
+            "full_path_frames_longest_utterance": longest,
+            "full_path_frames_mean": round(float(full.mean()), 1) if len(full) else 0.0,
+            # the launch lasts as long as its slowest workgroup, the utterance with the most
+            # full-path frames: an upper estimate of the cycles one such frame takes
+            "cycles_per_full_path_frame": round(search_avg_ms * 1e-3 * CLOCK_GHZ * 1e9
+                                                / max(1, longest), 0),
+            "note": "serial chain of frames per utterance on min(B,256) CUs: latency-bound, "
+                    "far from any throughput roof by construction"}
+
+
+def per_config(torch, binding, synth, dev, steps=20, cpu=True):
+    """Every named workload at every threshold it lists: whole-decode time over `steps` timed
+    steps, stage times, candidate statistics, workspace size, and the CPU oracle on all cores
+    and on one (bounded samples)."""
+    import numpy as np
+    if cpu:
+        import oracle
     out = []
-    for name, ww in synth.WORKLOADS.items():
-        if name == skip:
+    for name, w in synth.WORKLOADS.items():
+        if not name.startswith("cfg"):
             continue
-        job = Job(torch, binding, synth, ww, dev)
-        rr = ww.rel_thresholds[0]
-        pp = job.params(rr)
-        ms = event_times_ms(torch, lambda i: job.decode(pp), 5)
-        avg = sum(ms) / len(ms)
-        out.append({"workload": name, "B": ww.B, "T": ww.T, "V": ww.V, "beam": ww.beam,
-                    "rel_threshold": rr, "lm": bool(ww.use_lm), "frames": job.frames,
-                    "ms": round(avg, 4), "frames_per_s": round(job.frames / (avg * 1e-3), 1)})
+        job = Job(torch, binding, synth, w, dev)
+        for r in w.rel_thresholds:
+            progress(f"per_config {name} r={r}")
+            p = job.params(r)
+            for _ in range(3):
+                job.decode(p)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                job.decode(p)
+            torch.cuda.synchronize()
+            ms = (time.perf_counter() - t0) / steps * 1e3
+            prune_ms = event_times_ms(torch, lambda i: job.prune(r), 10)
+            search_ms = event_times_ms(torch, lambda i: job.search(p), 10)
+            st = job.stats_of(p)
+            full = full_path_frames(torch, binding, job, r)
+            search_avg = sum(search_ms) / len(search_ms)
+            rec = {"workload": name, "B": w.B, "T": w.T, "V": w.V, "beam": w.beam,
+                   "rel_threshold": r, "lm": bool(w.use_lm), "frames": job.frames, "steps": steps,
+                   "ms_per_step": round(ms, 4),
+                   "frames_per_s": round(job.frames / (ms * 1e-3), 1),
+                   "stage_us": {"prune": round(sum(prune_ms) / len(prune_ms) * 1e3, 2),
+                                "search": round(search_avg * 1e3, 2)},
+                   "mean_survivors": round(st["sum_survivors"] / max(1, st["frames"]), 3),
+                   "mean_candidates": round(st["sum_candidates"] / max(1, st["frames"]), 2),
+                   "peak_candidates": st["peak_candidates"],
+                   "mean_hypotheses": round(st["sum_beam"] / max(1, st["frames"]), 2),
+                   "full_path_frames_longest_utterance": int(full.max()),
+                   "cycles_per_full_path_frame": round(search_avg * 1e-3 * CLOCK_GHZ * 1e9
+                                                       / max(1, int(full.max())), 0),
+                   "workspace_bytes": int(job.ws.numel())}
+            if cpu:
+                lm = job.lm_host
+                rec["cpu_oracle"] = {
+                    "all_cores": oracle_rate(oracle, w, job.lp_host, job.ln_host, lm, r,
+                                             host_threads(), 2.5),
+                    "one_thread": oracle_rate(oracle, w, job.lp_host, job.ln_host, lm, r, 1, 1.5)}
+                rec["gpu_vs_cpu_oracle_all_cores"] = round(
+                    rec["frames_per_s"] / rec["cpu_oracle"]["all_cores"]["frames_per_s"], 1)
+            out.append(rec)
         del job
         torch.cuda.empty_cache()
+    # pruned vs unpruned per workload (GPU and CPU)
+    for rec in out:
+        base = next((x for x in out if x["workload"] == rec["workload"]
+                     and x["rel_threshold"] == 0.0), None)
+        if base is not None and rec["rel_threshold"] > 0.0:
+            rec["vs_unpruned"] = {
+                "gpu_speedup": round(base["ms_per_step"] / rec["ms_per_step"], 2),
+                "mean_candidates_ratio": round(base["mean_candidates"] / rec["mean_candidates"], 2),
+                "peak_candidates_ratio": round(base["peak_candidates"] / max(1, rec["peak_candidates"]), 2)}
+            if cpu:
+                rec["vs_unpruned"]["cpu_oracle_speedup"] = round(
+                    rec["cpu_oracle"]["all_cores"]["frames_per_s"]
+                    / base["cpu_oracle"]["all_cores"]["frames_per_s"], 2)
     return out
-
-
-def cpu_baseline(synth, w, r, frames_budget_s=12.0):
-    import oracle
-    threads = max(1, min(16, os.cpu_count() or 1))
-    lp, ln = synth.make_emissions(w)
-    lm = synth.make_bigram_lm(w.V) if w.use_lm else None
-    kw = dict(lm_table=lm, lm_weight=w.lm_weight, insertion_bonus=w.insertion_bonus)
-    # pruned search, whole batch, repeated until a few seconds have passed
-    reps, t0 = 0, time.perf_counter()
-    while True:
-        oracle.decode(lp, ln, w.beam, r, n_threads=threads, **kw)
-        reps += 1
-        dt = time.perf_counter() - t0
-        if dt > frames_budget_s / 3 or reps >= 20:
-            break
-    fps = reps * int(ln.sum()) / dt
-    # one thread, a quarter of the batch
-    q = max(1, w.B // 4)
-    t0 = time.perf_counter()
-    oracle.decode(lp[:q], ln[:q], w.beam, r, n_threads=1, **kw)
-    fps_1t = int(ln[:q].sum()) / (time.perf_counter() - t0)
-    # unpruned search on a sample
-    q0 = max(1, w.B // 8)
-    t0 = time.perf_counter()
-    oracle.decode(lp[:q0], ln[:q0], w.beam, 0.0, n_threads=threads, **kw)
-    fps_unpruned = int(ln[:q0].sum()) / (time.perf_counter() - t0)
-    return {"value": round(fps, 1), "unit": "frames/s", "cores": threads, "kind": "oracle",
-            "sample": f"{w.name}: whole batch x{reps} at r={r} on {threads} threads; "
-                      f"1-thread figure on the first {q} utterances; unpruned (r=0) on the "
-                      f"first {q0} utterances",
-            "one_thread_frames_per_s": round(fps_1t, 1),
-            "unpruned_frames_per_s": round(fps_unpruned, 1),
-            "pruned_vs_unpruned_speedup": round(fps / fps_unpruned, 2)}
 
 
 def source_digest(*names):
@@ -454,6 +613,55 @@ def recorded_traffic(kernel, workload):
     if rec.get("source_sha256") != source_digest(*rec.get("sources", [])):
         return None
     return rec.get("hbm_bytes_per_launch")
+
+
+PHASES = (  # (index in fltop_stats.phase_clocks, what the span covers), in pipeline order
+    (0, "frame set-up: header from the LDS ring, survivors staged"),
+    (8, "first extension candidate evaluated"),
+    (1, "stay candidate evaluated (two log-sum-exps)"),
+    (2, "histogram of all candidates, barrier 1"),
+    (3, "selection: scan of the histogram, threshold"),
+    (4, "exact ranking of the boundary bucket (two more barriers; rare)"),
+    (9, "slot allocation in the next beam"),
+    (5, "emit into the next beam, trie stores, barrier 2"),
+    (10, "parent / children links of the new beam"),
+    (6, "housekeeping, barrier 3"),
+    (7, "runs of blank-only frames (per run)"),
+)
+
+
+def phase_clock_table(args, torch, binding, synth, dev):
+    """Cycles per full-path frame and phase, per wavefront group, from the profiling build."""
+    w = synth.WORKLOADS[args.workload]
+    r = args.rel_threshold
+    job = Job(torch, binding, synth, w, dev)
+    p = job.params(r)
+    for _ in range(2):
+        job.decode(p)
+    st = job.stats_of(p)
+    clk = [st.get(f"clk{i}", 0) for i in range(64)]
+    if not any(clk):
+        print("bench.py --phase-clocks: the loaded library keeps no phase clocks; build it with "
+              "`python -m paper_2510_09085_amd.build --define FLTOP_PHASE_CLOCKS --out X.so` and "
+              "set FLTOP_CTC_LIB=X.so", file=sys.stderr)
+        sys.exit(2)
+    full = full_path_frames(torch, binding, job, r)
+    n_full = int(full.sum())
+    ms = event_times_ms(torch, lambda i: job.search(p), 10)
+    print(f"# search stage of {w.name} (B={w.B}, T={w.T}, V={w.V}, beam={w.beam}, r={r}): shader-clock "
+          f"cycles per full-path frame, by phase")
+    print(f"# {st['frames']} frames, {n_full} of them full-path (not blank-only); search stage "
+          f"{sum(ms) / len(ms) * 1e3:.1f} us with the clocks compiled in")
+    print(f"# columns: wavefront group 0 (stay candidates), 1, 2 (first extension candidates), 3; "
+          f"lane 0 of each group's first wavefront")
+    print(f"{'phase':66s} {'g0':>8s} {'g1':>8s} {'g2':>8s} {'g3':>8s}")
+    totals = [0.0] * 4
+    for idx, what in PHASES:
+        row = [clk[g * 16 + idx] / max(1, n_full) for g in range(4)]
+        if idx != 7:
+            totals = [a + b for a, b in zip(totals, row)]
+        print(f"{what:66s} " + " ".join(f"{x:8.0f}" for x in row))
+    print(f"{'sum without the blank-only runs':66s} " + " ".join(f"{x:8.0f}" for x in totals))
 
 
 def counter_probe(args, torch, binding, synth, dev):
@@ -506,8 +714,105 @@ def counter_probe(args, torch, binding, synth, dev):
     print(json.dumps(out))
 
 
+# ---- rocprofv3 output databases -> the short text tables kept under profiles/ ------------
+def _short_kernel_name(name):
+    import re
+    name = name.replace("fltop::(anonymous namespace)::", "fltop::")
+    name = re.sub(r"^void ", "", name)
+    return re.sub(r"\((?!anonymous).*$", "", name)[:64]
+
+
+def summarise_kernels(db, top=20):
+    """Per (kernel, grid): launches and total / average / min / max duration."""
+    import sqlite3
+    con = sqlite3.connect(db)
+    rows = con.execute(
+        "select name, grid_x / max(workgroup_x, 1) * max(grid_y / max(workgroup_y, 1), 1), "
+        "count(*), sum(end - start), avg(end - start), min(end - start), max(end - start) "
+        "from kernels group by 1, 2 order by 4 desc").fetchall()
+    total = sum(r[3] for r in rows) or 1
+    out = [f"{'kernel':64s} {'workgroups':>10s} {'calls':>6s} {'total_us':>11s} {'avg_us':>9s} "
+           f"{'min_us':>9s} {'max_us':>9s} {'%':>6s}"]
+    for name, wgs, calls, tot, avg, mn, mx in rows[:top]:
+        out.append(f"{_short_kernel_name(name):64s} {int(wgs):10d} {calls:6d} {tot / 1e3:11.1f} "
+                   f"{avg / 1e3:9.2f} {mn / 1e3:9.2f} {mx / 1e3:9.2f} {100 * tot / total:6.2f}")
+    return "\n".join(out)
+
+
+def _counter_rows(db, substr):
+    import sqlite3
+    con = sqlite3.connect(db)
+    rows = con.execute("select kernel_name, counter_name, value, duration from counters_collection "
+                       "order by dispatch_id").fetchall()
+    return [r for r in rows if substr in r[0]]
+
+
+def summarise_counters(db, substr=""):
+    """Mean value per launch of every collected counter, per kernel whose name contains substr."""
+    from collections import defaultdict
+    acc, dur = defaultdict(list), defaultdict(list)
+    for name, counter, value, duration in _counter_rows(db, substr):
+        acc[(_short_kernel_name(name), counter)].append(value)
+        dur[_short_kernel_name(name)].append(duration)
+    out = [f"{'kernel':56s} {'counter':24s} {'launches':>8s} {'mean per launch':>18s}"]
+    for (name, counter), vals in sorted(acc.items()):
+        out.append(f"{name:56s} {counter:24s} {len(vals):8d} {sum(vals) / len(vals):18.1f}")
+    for name, d in sorted(dur.items()):
+        out.append(f"{name:56s} {'duration_us':24s} {len(d):8d} {sum(d) / len(d) / 1e3:18.2f}")
+    return "\n".join(out)
+
+
+def summarise_traffic(fetch_db, write_db, probe_json, substr, out_json):
+    """HBM bytes per launch of one kernel: FETCH_SIZE and WRITE_SIZE (KiB per dispatch), each
+    scaled by what the same counter reads for the plain device copy of known size that
+    --counter-probe runs beside it; writes the record recorded_traffic() looks up."""
+    with open(probe_json) as fh:
+        probe = json.load(fh)
+    copy_bytes = probe["copy_bytes_each_way"]
+
+    def mean_kib(db, sub, counter, only_full_copies=False):
+        vals = [v for _, c, v, _ in _counter_rows(db, sub) if c == counter]
+        if only_full_copies:  # the calibration copies are the largest ones in the run
+            vals = [v for v in vals if v >= 0.9 * max(vals)]
+        return sum(vals) / len(vals)
+
+    f_copy = mean_kib(fetch_db, "copyBuffer", "FETCH_SIZE", True) * 1024
+    w_copy = mean_kib(write_db, "copyBuffer", "WRITE_SIZE", True) * 1024
+    f_scale, w_scale = copy_bytes / f_copy, copy_bytes / w_copy
+    f_k = mean_kib(fetch_db, substr, "FETCH_SIZE") * 1024 * f_scale
+    w_k = mean_kib(write_db, substr, "WRITE_SIZE") * 1024 * w_scale
+    rec = {"kernel": substr, "workload": probe["workload"], "rel_threshold": probe["rel_threshold"],
+           "fetch_scale_from_copy": round(f_scale, 4), "write_scale_from_copy": round(w_scale, 4),
+           "hbm_read_bytes_per_launch": round(f_k), "hbm_write_bytes_per_launch": round(w_k),
+           "hbm_bytes_per_launch": round(f_k + w_k),
+           "sources": probe["sources"], "source_sha256": probe["source_sha256"]}
+    for key in ("emission_bytes_per_launch", "written_bytes_approx", "frames"):
+        if key in probe:
+            rec[key] = probe[key]
+    with open(out_json, "w") as fh:
+        json.dump(rec, fh, indent=1)
+        fh.write("\n")
+    return json.dumps(rec, indent=1)
+
+
+def summarise(argv):
+    kind = argv[0]
+    if kind == "kernels" and len(argv) >= 2:
+        print(summarise_kernels(argv[1], int(argv[2]) if len(argv) > 2 else 20))
+    elif kind == "counters" and len(argv) >= 2:
+        print(summarise_counters(argv[1], argv[2] if len(argv) > 2 else ""))
+    elif kind == "traffic" and len(argv) == 6:
+        print(summarise_traffic(*argv[1:6]))
+    else:
+        print(__doc__, file=sys.stderr)
+        sys.exit(2)
+
+
 def main():
     args = parse_args()
+    if args.summarise:
+        summarise(args.summarise)
+        return
     if args.gpus != 1:
         print("bench.py: this decoder runs on ONE GPU (utterances are independent; a multi-GPU "
               "run would be N separate calls on N slices of the batch). Use --gpus 1.",
@@ -524,9 +829,13 @@ def main():
     if args.counter_probe:
         counter_probe(args, torch, binding, synth, dev)
         return
+    if args.phase_clocks:
+        phase_clock_table(args, torch, binding, synth, dev)
+        return
     w = synth.WORKLOADS[args.workload]
     r = args.rel_threshold
 
+    progress(f"headline {w.name} r={r}: inputs")
     job = Job(torch, binding, synth, w, dev)
     p = job.params(r)
 
@@ -549,16 +858,8 @@ def main():
     st = job.stats_of(p)
     search_avg = sum(search_ms) / len(search_ms)
     prune_avg = sum(prune_ms) / len(prune_ms)
-    flops = FLOP_PER_CANDIDATE * st["sum_candidates"]
-    tflops = flops / (search_avg * 1e-3) / 1e12
-    roofline = {"kernel": "beam_kernel (search stage)", "bound": "alu",
-                "achieved": round(tflops, 6), "peak": FP64_VECTOR_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(tflops / FP64_VECTOR_TFLOPS, 8),
-                "traffic": recorded_traffic("beam_kernel", w.name),
-                "avg_launch_us": round(search_avg * 1e3, 2),
-                "algorithmic_flop": flops,
-                "note": "serial chain of T frames per utterance on min(B,256) CUs: "
-                        "latency-bound, far from any throughput roof by construction"}
+    roofline = search_roofline(torch, binding, job, r, st, search_avg)
+    progress(f"headline done: {ms_per_step:.4f} ms per step")
 
     result = {
         "metric": "decoded frames/sec (1 GPU)", "value": round(fps, 1), "unit": "frames/s",
@@ -569,73 +870,78 @@ def main():
                    "rel_threshold": r, "frames": job.frames, "lm": bool(w.use_lm)},
         "audio_seconds_per_s": round(fps / synth.FRAMES_PER_SECOND, 1),
         "stage_us": {"prune": round(prune_avg * 1e3, 2), "search": round(search_avg * 1e3, 2)},
+        "mean_survivors": round(st["sum_survivors"] / max(1, st["frames"]), 3),
+        "mean_candidates": round(st["sum_candidates"] / max(1, st["frames"]), 2),
+        "workspace_bytes": int(job.ws.numel()),
         "roofline": roofline,
     }
+    del job
+    torch.cuda.empty_cache()
 
     if not args.skip_extras:
-        # ---- independent batches on separate streams (first among the extras: which
-        #      hardware queue a new stream lands on depends on what the process did before)
-        result["concurrent_streams"] = concurrent_streams(torch, binding, job, r)
-        # ---- pruned vs unpruned on this workload ------------------------------------
+        # ---- every named workload, every listed threshold, GPU and CPU oracle -------------
+        result["per_config"] = per_config(torch, binding, synth, dev, steps=20,
+                                          cpu=not args.skip_cpu_baseline)
+        # ---- emission-read bandwidth of the prune stage (the HBM-bound kernel) ------------
+        reads = []
+        for name in ("cfg1_single", "cfg2_batch64", "cfg3_varlen256", "cfg4_subword1024",
+                     "cfg5_bigram_lm"):
+            progress(f"emission read {name}")
+            reads.append(emission_read_roofline(torch, binding, synth, synth.WORKLOADS[name],
+                                                0.01, dev))
+            torch.cuda.empty_cache()
+        result["roofline_emission_read"] = next(x for x in reads if x["workload"] == w.name) \
+            if any(x["workload"] == w.name for x in reads) else reads[2]
+        result["emission_read_all_workloads"] = reads
+        # ---- further figures on the 64-utterance workload ---------------------------------
+        w2 = synth.WORKLOADS["cfg2_batch64"]
+        r2 = 0.01
+        job2 = Job(torch, binding, synth, w2, dev)
+        extras = {"workload": w2.name, "rel_threshold": r2}
+        # independent batches on separate streams (first: which hardware queue a new stream
+        # lands on depends on what the process did before)
+        progress("cfg2 extras: concurrent streams, selection sweep")
+        extras["concurrent_streams"] = concurrent_streams(torch, binding, job2, r2)
         sweep = []
-        for rr in w.rel_thresholds:
-            pp = job.params(rr)
-            ms = event_times_ms(torch, lambda i: job.decode(pp), 10)
-            s = job.stats_of(pp)
-            avg = sum(ms) / len(ms)
-            sweep.append({
-                "rel_threshold": rr, "ms": round(avg, 4),
-                "frames_per_s": round(job.frames / (avg * 1e-3), 1),
-                "mean_survivors": round(s["sum_survivors"] / s["frames"], 3),
-                "mean_candidates": round(s["sum_candidates"] / s["frames"], 2),
-                "peak_candidates": s["peak_candidates"],
-                "peak_candidate_bytes": s["peak_candidates"] * CAND_RECORD_BYTES,
-                "survivor_record_bytes": prune_written_bytes(s),
-                "select_passes_per_frame": round(s["select_passes"] / s["frames"], 3),
-                "exact_rankings_per_frame": round(s["exact_rankings"] / s["frames"], 3),
-            })
-        result["threshold_sweep"] = sweep
-        base = next((x for x in sweep if x["rel_threshold"] == 0.0), None)
-        mine = next((x for x in sweep if x["rel_threshold"] == r), None)
-        if base and mine:
-            result["pruned_vs_unpruned"] = {
-                "speedup": round(base["ms"] / mine["ms"], 2),
-                "mean_candidates_ratio": round(base["mean_candidates"] / mine["mean_candidates"], 2),
-                "peak_candidate_bytes_ratio": round(
-                    base["peak_candidate_bytes"] / max(1, mine["peak_candidate_bytes"]), 2),
-                "survivor_record_bytes_ratio": round(
-                    base["survivor_record_bytes"] / mine["survivor_record_bytes"], 2),
-            }
-        # ---- the paper's three arms, with its score window (beam-threshold 25) and a
-        #      tighter one that actually bites at this beam size
-        result["paper_arms"] = {"window_25": paper_arms(torch, binding, job, 25.0),
-                                "window_6": paper_arms(torch, binding, job, 6.0)}
-        # ... and with the largest beam the library takes (the paper's baseline uses 1000)
+        for rr in w2.rel_thresholds:
+            pp = job2.params(rr)
+            s = job2.stats_of(pp)
+            sweep.append({"rel_threshold": rr,
+                          "peak_candidates": s["peak_candidates"],
+                          "peak_candidate_records_bytes": s["peak_candidates"] * CAND_RECORD_BYTES,
+                          "survivor_record_bytes": prune_written_bytes(s),
+                          "select_passes_per_frame": round(s["select_passes"] / s["frames"], 3),
+                          "exact_rankings_per_frame": round(s["exact_rankings"] / s["frames"], 3)})
+        extras["selection_sweep"] = sweep
+        extras["candidate_record_note"] = (
+            "candidates are never stored (they live in registers and LDS); "
+            "peak_candidate_records_bytes is the candidate COUNT times a 24-byte record "
+            "(score, hash, source entry, token), what a stored candidate set would take")
+        # the paper's three arms, with its score window (beam-threshold 25) and a tighter one
+        # that actually bites at this beam size ...
+        progress("cfg2 extras: paper arms")
+        extras["paper_arms"] = {"window_25": paper_arms(torch, binding, job2, 25.0),
+                                "window_6": paper_arms(torch, binding, job2, 6.0)}
+        # ... and with the paper's beam of 1000 where the library takes it, else its largest
         import dataclasses
-        wide_job = Job(torch, binding, synth, dataclasses.replace(w, beam=binding.MAX_BEAM), dev)
-        result["paper_arms"][f"beam{binding.MAX_BEAM}_window_25"] = paper_arms(
-            torch, binding, wide_job, 25.0)
+        big_beam = min(1000, binding.MAX_BEAM)
+        wide_job = Job(torch, binding, synth, dataclasses.replace(w2, beam=big_beam), dev)
+        extras["paper_arms"][f"beam{big_beam}_window_25"] = paper_arms(torch, binding, wide_job,
+                                                                      25.0)
         del wide_job
-        result["batch_scaling"] = batch_scaling(torch, binding, job, r)
-        result["streaming"] = streaming_latency(torch, binding, synth, w, r, dev)
+        progress("cfg2 extras: batch scaling, streaming")
+        extras["batch_scaling"] = batch_scaling(torch, binding, job2, r2)
+        del job2
+        torch.cuda.empty_cache()
+        extras["streaming"] = streaming_latency(torch, binding, synth, w2, r2, dev)
+        result["cfg2_extras"] = extras
         result["paper_context"] = ("paper reports 10.5x runtime speedup and 2.78x fewer beams "
                                    "(FLToP N=4,R=0.007 vs all-32-token baseline) for a CPU "
                                    "flashlight/KenLM decoder on LibriSpeech, wav2vec2-large "
                                    "encoder on an L4; context only")
-        # ---- emission-read bandwidth of the prune stage --------------------------------
-        del job
-        torch.cuda.empty_cache()
-        reads = []
-        for name in (w.name, "cfg3_varlen256", "cfg4_subword1024"):
-            ww = synth.WORKLOADS[name]
-            rr = r if name == w.name else 0.01
-            reads.append(emission_read_roofline(torch, binding, synth, ww, rr, dev))
-            torch.cuda.empty_cache()
-        result["roofline_emission_read"] = reads[0]
-        result["emission_read_other_workloads"] = reads[1:]
-        result["other_workloads"] = other_workloads(torch, binding, synth, dev, w.name)
 
     if not args.skip_cpu_baseline:
+        progress("cpu baseline (oracle on the host cores)")
         result["cpu_baseline"] = cpu_baseline(synth, w, r)
         result["gpu_vs_cpu_oracle"] = round(fps / result["cpu_baseline"]["value"], 1)
 

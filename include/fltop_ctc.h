@@ -33,7 +33,8 @@
  *
  * Conventions: "dev" = device (HBM) pointer, "host" = host pointer.  Arrays are
  * row-major and densely packed.  The caller owns every buffer; the library
- * allocates nothing, keeps no decoding state between calls and may be called
+ * allocates nothing, keeps no decoding state between calls (it only remembers, per
+ * device, constants such as the number of compute units) and may be called
  * concurrently on different streams with different workspaces.  All work is
  * enqueued on `stream` as kernel launches only (so a call may be captured in a HIP
  * graph); no entry point synchronises with the host, so outputs are valid once the
@@ -53,7 +54,7 @@ extern "C" {
 
 #define FLTOP_OK                  0
 #define FLTOP_ERR_NULL_POINTER   -1  /* a required pointer is NULL                          */
-#define FLTOP_ERR_BAD_SHAPE      -2  /* B < 1, T < 1 or V < 2                               */
+#define FLTOP_ERR_BAD_SHAPE      -2  /* B < 1, T < 1, V < 2, or T * beam >= 2^31            */
 #define FLTOP_ERR_BAD_BEAM       -3  /* beam < 1 or beam > FLTOP_MAX_BEAM                   */
 #define FLTOP_ERR_BAD_THRESHOLD  -4  /* rel_threshold outside [0, 1] or NaN                 */
 #define FLTOP_ERR_WORKSPACE      -5  /* workspace smaller than fltop_ctc_workspace_bytes()  */
@@ -101,12 +102,17 @@ typedef struct fltop_stats {
     uint64_t sum_candidates;    /* sum over frames of distinct live candidate prefixes         */
     uint64_t peak_candidates;   /* max over frames (and utterances) of the same                */
     uint64_t sum_beam;          /* sum over frames of entries kept by SelectTopK               */
-    uint64_t select_passes;     /* histogram passes spent in the top-`beam` selection          */
-    uint64_t exact_rankings;    /* selections that needed the exact (score, hash) ranking      */
-    uint64_t overflow_drops;    /* entries dropped because a hash collision overfilled a beam  */
-    uint64_t phase_clocks[16];  /* diagnostic: shader-clock cycles per phase of the search stage,
-                                   summed over workgroups; filled only by a library built with
-                                   -DFLTOP_PHASE_CLOCKS, otherwise left untouched              */
+    uint64_t select_passes;     /* diagnostic: histogram passes of the top-`beam` selection    */
+    uint64_t exact_rankings;    /* diagnostic: selections that needed the exact (score, hash)
+                                   ranking                                                     */
+    uint64_t overflow_drops;    /* entries dropped because a hash collision overfilled a beam
+                                   (0 unless two different prefixes share a 64-bit hash)       */
+#ifdef FLTOP_PHASE_CLOCKS
+    uint64_t phase_clocks[64];  /* profiling builds only (library AND caller compiled with
+                                   -DFLTOP_PHASE_CLOCKS): shader-clock cycles per phase of the
+                                   search stage, [wavefront group 0..3][phase 0..15], summed
+                                   over workgroups                                             */
+#endif
 } fltop_stats;
 
 /* Bytes of device workspace fltop_ctc_decode / fltop_ctc_prune need for these

@@ -30,6 +30,7 @@ class OracleStats(ctypes.Structure):
         ("max_addends", ctypes.c_int64),
         ("hash_collisions", ctypes.c_int64),
         ("min_cut_margin", ctypes.c_double),
+        ("min_decision_margin", ctypes.c_double),
     ]
 
     def as_dict(self):
@@ -81,7 +82,7 @@ def load():
                                         ctypes.c_int32, ctypes.c_int32, ctypes.c_float,
                                         ctypes.c_int32, ctypes.c_double, f32p,
                                         ctypes.c_float, ctypes.c_float, ctypes.c_int32, i32p,
-                                        i32p, f64p, i32p, i32p, ctypes.POINTER(OracleStats),
+                                        i32p, f64p, i32p, i32p, f64p, ctypes.POINTER(OracleStats),
                                         ctypes.c_int32]
     lib.fltop_oracle_decode_beam.restype = ctypes.c_int
     lib.fltop_oracle_token_ranks.restype = ctypes.c_int
@@ -154,18 +155,21 @@ def decode(logprobs: np.ndarray, lengths: np.ndarray, beam: int, rel_threshold: 
     i32p = ctypes.POINTER(ctypes.c_int32)
     tok_frames = np.full((B, max(T, 1)), -1, dtype=np.int32) if traces else None
     frame_beam = np.full((B, max(T, 1)), -1, dtype=np.int32) if traces else None
+    margins = np.full(B, np.inf, dtype=np.float64)
     rc = load().fltop_oracle_decode(
         lp_p, ln_p, B, T, V, int(beam), float(rel_threshold), int(top_n), float(beam_threshold),
         lm_p, float(lm_weight), float(insertion_bonus), int(variant),
         out_tok.ctypes.data_as(i32p), out_len.ctypes.data_as(i32p),
         out_sc.ctypes.data_as(ctypes.POINTER(ctypes.c_double)),
         tok_frames.ctypes.data_as(i32p) if traces else None,
-        frame_beam.ctypes.data_as(i32p) if traces else None, ctypes.byref(st),
+        frame_beam.ctypes.data_as(i32p) if traces else None,
+        margins.ctypes.data_as(ctypes.POINTER(ctypes.c_double)), ctypes.byref(st),
         int(n_threads))
     if rc != 0:
         raise ValueError("fltop_oracle_decode: bad arguments")
     toks = [out_tok[b, :out_len[b]].tolist() for b in range(B)]
     stats = st.as_dict()
+    stats["margins"] = margins.tolist()  # per utterance: smallest score gap that decided anything
     if traces:
         stats["token_frames"] = [tok_frames[b, :out_len[b]].tolist() for b in range(B)]
         stats["frame_beam"] = frame_beam[:, :T]

@@ -132,10 +132,15 @@ struct LocalStats {
     int64_t frames, sum_survivors, sum_candidates, peak_candidates, sum_beam, max_addends,
         hash_collisions;
     double min_cut_margin;
+    /* smallest score gap that decided anything: the beam cut, the window floor (distance of
+     * the nearest candidate on either side), the choice of the final best prefix.  0 means
+     * an exact tie, which the hash order resolved.  Reporting only. */
+    double min_decision_margin;
     LocalStats()
         : frames(0), sum_survivors(0), sum_candidates(0), peak_candidates(0), sum_beam(0),
           max_addends(0), hash_collisions(0),
-          min_cut_margin(std::numeric_limits<double>::infinity()) {}
+          min_cut_margin(std::numeric_limits<double>::infinity()),
+          min_decision_margin(std::numeric_limits<double>::infinity()) {}
 };
 
 /* SelectTopK of Alg. 1: rank the live candidates of `next` (score desc, hash asc), drop
@@ -164,12 +169,16 @@ Beam keep_best(const Beam& next, int32_t beam, double beam_threshold, LocalStats
         const double floor_score = order[0].total - beam_threshold;
         size_t inside = 0;
         while (inside < order.size() && order[inside].total >= floor_score) ++inside;
+        for (size_t i = 1; i < order.size(); ++i) /* order[0] is the window's own anchor */
+            st.min_decision_margin =
+                std::min(st.min_decision_margin, std::fabs(order[i].total - floor_score));
         order.resize(inside); /* the list is sorted, so the window is a leading run */
         n = (int64_t)order.size();
     }
     if (n > beam) {
         double margin = order[beam - 1].total - order[beam].total;
         if (margin < st.min_cut_margin) st.min_cut_margin = margin;
+        if (margin < st.min_decision_margin) st.min_decision_margin = margin;
         order.resize(beam);
     }
     st.sum_beam += (int64_t)order.size();
@@ -407,7 +416,8 @@ extern "C" int fltop_oracle_decode(const float* logprobs, const int32_t* lengths
                                    float lm_weight, float insertion_bonus, int32_t variant,
                                    int32_t* out_tokens, int32_t* out_lengths, double* out_scores,
                                    int32_t* out_token_frames, int32_t* frame_beam,
-                                   fltop_oracle_stats* stats, int32_t n_threads) {
+                                   double* out_margins, fltop_oracle_stats* stats,
+                                   int32_t n_threads) {
     if (bad_common(logprobs, T, V, beam, rel_threshold, top_n, beam_threshold, variant))
         return -1;
     if (variant == FLTOP_ORACLE_TEXTBOOK && (out_token_frames || frame_beam)) return -1;
@@ -435,9 +445,23 @@ extern "C" int fltop_oracle_decode(const float* logprobs, const int32_t* lengths
             spec.top_n = top_n;
             spec.beam_threshold = beam_threshold;
             spec.frame_beam = frame_beam ? frame_beam + (int64_t)b * T : 0;
+            LocalStats one;
             Beam fin = decode_one(logprobs + (int64_t)b * T * V, lengths[b], V, spec, lm, variant,
-                                  mine);
+                                  one);
             std::vector<Ranked> order = rank_all(fin);
+            if (order.size() > 1)
+                one.min_decision_margin =
+                    std::min(one.min_decision_margin, order[0].total - order[1].total);
+            if (out_margins) out_margins[b] = one.min_decision_margin;
+            mine.frames += one.frames;
+            mine.sum_survivors += one.sum_survivors;
+            mine.sum_candidates += one.sum_candidates;
+            mine.sum_beam += one.sum_beam;
+            mine.hash_collisions += one.hash_collisions;
+            mine.peak_candidates = std::max(mine.peak_candidates, one.peak_candidates);
+            mine.max_addends = std::max(mine.max_addends, one.max_addends);
+            mine.min_cut_margin = std::min(mine.min_cut_margin, one.min_cut_margin);
+            mine.min_decision_margin = std::min(mine.min_decision_margin, one.min_decision_margin);
             int32_t* dst = out_tokens + (int64_t)b * T;
             if (order.empty()) { /* every route died (a frame of all -inf) */
                 out_lengths[b] = 0;
@@ -463,6 +487,7 @@ extern "C" int fltop_oracle_decode(const float* logprobs, const int32_t* lengths
         all.peak_candidates = std::max(all.peak_candidates, mine.peak_candidates);
         all.max_addends = std::max(all.max_addends, mine.max_addends);
         all.min_cut_margin = std::min(all.min_cut_margin, mine.min_cut_margin);
+        all.min_decision_margin = std::min(all.min_decision_margin, mine.min_decision_margin);
     };
     std::vector<std::thread> pool;
     for (int32_t i = 1; i < n_threads; ++i) pool.emplace_back(worker);
@@ -478,6 +503,7 @@ extern "C" int fltop_oracle_decode(const float* logprobs, const int32_t* lengths
         stats->max_addends = all.max_addends;
         stats->hash_collisions = all.hash_collisions;
         stats->min_cut_margin = all.min_cut_margin;
+        stats->min_decision_margin = all.min_decision_margin;
     }
     return 0;
 }

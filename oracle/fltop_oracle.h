@@ -42,6 +42,10 @@ typedef struct fltop_oracle_stats {
     int64_t max_addends;      /* most terms ever log-summed into one p_b or p_nb           */
     int64_t hash_collisions;  /* distinct candidate prefixes of one frame sharing a hash   */
     double  min_cut_margin;   /* min over frames of score[beam-1] - score[beam]            */
+    double  min_decision_margin; /* smallest score gap that decided anything: a beam cut, the
+                                    window floor (nearest candidate on either side), the final
+                                    choice of the best prefix; 0 = an exact tie that the hash
+                                    order resolved; +inf = nothing was ever cut              */
 } fltop_oracle_stats;
 
 /* Variant selector for the decode entry points. */
@@ -75,6 +79,7 @@ int fltop_oracle_survivors(const float* logprobs, int64_t n_frames, int32_t V,
  *  out_token_frames NULL or [B,T]: for token i of the best prefix, the frame at which
  *  the prefix of length i+1 entered the beam (on the lineage of the final entry),
  *  frame_beam NULL or [B,T]: number of beam entries kept after each frame,
+ *  out_margins NULL or [B]: min_decision_margin (see the stats) of each utterance by itself,
  *  stats NULL or one struct accumulated over the batch, n_threads >= 1.
  * The TEXTBOOK variant takes neither top_n, beam_threshold nor the two traces.
  * Returns 0, or -1 on bad arguments. */
@@ -84,7 +89,7 @@ int fltop_oracle_decode(const float* logprobs, const int32_t* lengths,
                         const float* lm_table, float lm_weight, float insertion_bonus,
                         int32_t variant, int32_t* out_tokens, int32_t* out_lengths,
                         double* out_scores, int32_t* out_token_frames, int32_t* frame_beam,
-                        fltop_oracle_stats* stats, int32_t n_threads);
+                        double* out_margins, fltop_oracle_stats* stats, int32_t n_threads);
 
 /* Single utterance, whole final beam in rank order (score desc, hash asc).
  *  logprobs [T,V]; beam_tokens [max_entries, T]; beam_lengths, beam_pb, beam_pnb

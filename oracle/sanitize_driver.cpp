@@ -91,13 +91,13 @@ int main() {
             if (textbook && (c.top_n > 0 || c.window > 0.0)) continue;
             std::vector<int32_t> out_tok((size_t)c.B * c.T), out_len(c.B);
             std::vector<int32_t> tf((size_t)c.B * c.T), fb((size_t)c.B * c.T);
-            std::vector<double> score(c.B);
+            std::vector<double> score(c.B), margins(c.B);
             fltop_oracle_stats st = {};
             const int rc = fltop_oracle_decode(
                 lp.data(), len.data(), c.B, c.T, c.V, c.beam, textbook ? 0.0f : c.r, c.top_n,
                 c.window, c.lm ? lm.data() : nullptr, 0.5f, 1.0f, variant, out_tok.data(),
                 out_len.data(), score.data(), textbook ? nullptr : tf.data(),
-                textbook ? nullptr : fb.data(), &st, 1 + variant * 2);
+                textbook ? nullptr : fb.data(), margins.data(), &st, 1 + variant * 2);
             if (rc != 0) return fail("decode status");
             for (int b = 0; b < c.B; ++b) {
                 if (out_len[b] < 0 || out_len[b] > len[b]) return fail("output length out of range");
@@ -140,10 +140,10 @@ int main() {
     int32_t one_len = 4, tok[4], ol;
     double sc;
     if (fltop_oracle_decode(lp.data(), &one_len, 1, 4, 4, 0, 0.01f, 0, 0.0, nullptr, 0.f, 0.f, 0, tok,
-                            &ol, &sc, nullptr, nullptr, nullptr, 1) != -1)
+                            &ol, &sc, nullptr, nullptr, nullptr, nullptr, 1) != -1)
         return fail("beam 0 accepted");
     if (fltop_oracle_decode(lp.data(), &one_len, 1, 4, 4, 2, 2.0f, 0, 0.0, nullptr, 0.f, 0.f, 0, tok,
-                            &ol, &sc, nullptr, nullptr, nullptr, 1) != -1)
+                            &ol, &sc, nullptr, nullptr, nullptr, nullptr, 1) != -1)
         return fail("r > 1 accepted");
     const int32_t empty[1] = {0};
     if (fltop_oracle_prefix_hash(empty, 0) != 0x9E3779B97F4A7C15ull) return fail("hash of empty");

@@ -45,8 +45,10 @@ class FltopParams(ctypes.Structure):
 
 
 STATS_FIELDS = ("frames", "sum_survivors", "sum_candidates", "peak_candidates", "sum_beam",
-                "select_passes", "exact_rankings", "overflow_drops",
-                *[f"clk{i}" for i in range(16)])
+                "select_passes", "exact_rankings", "overflow_drops")
+# words to allocate for a fltop_stats block: the eight counters, and room for the 4 x 16 phase
+# clocks that a profiling build of the library (-DFLTOP_PHASE_CLOCKS) appends
+STATS_WORDS = len(STATS_FIELDS) + 64
 
 _lib = None
 
@@ -169,7 +171,7 @@ def decode(logprobs: torch.Tensor, lengths: torch.Tensor, beam: int, rel_thresho
            stream=None) -> dict:
     """fltop_ctc_decode on device tensors.  Returns device tensors (no host sync):
     tokens [B,T] int32, lengths [B] int32, scores [B] fp32, and optionally stats
-    (uint64 [8], see STATS_FIELDS), the n-best export, and the statistics traces
+    (uint64, see STATS_FIELDS), the n-best export, and the statistics traces
     (frame_beam [B,T], token_frames [B,T], both int32 and -1 where nothing was written)."""
     _check_inputs(logprobs, lengths)
     B, T, V = logprobs.shape
@@ -211,7 +213,7 @@ def decode(logprobs: torch.Tensor, lengths: torch.Tensor, beam: int, rel_thresho
         p.out_token_frames = out["token_frames"].data_ptr()
     stats = None
     if want_stats:
-        stats = torch.zeros(len(STATS_FIELDS), dtype=torch.int64, device=dev)
+        stats = torch.zeros(STATS_WORDS, dtype=torch.int64, device=dev)
         out["stats"] = stats
     rc = decode_raw(logprobs, lengths, p, workspace, workspace.numel(), out["tokens"],
                     out["lengths"], out["scores"], stats, stream)
@@ -289,7 +291,7 @@ class Stream:
         self.tokens = torch.full((B, T_total), -1, dtype=torch.int32, device=device)
         self.lengths = torch.zeros(B, dtype=torch.int32, device=device)
         self.scores = torch.zeros(B, dtype=torch.float32, device=device)
-        self.stats = torch.zeros(len(STATS_FIELDS), dtype=torch.int64, device=device)
+        self.stats = torch.zeros(STATS_WORDS, dtype=torch.int64, device=device)
         p = FltopParams()
         p.beam = int(beam)
         p.rel_threshold = float(rel_threshold)
@@ -346,4 +348,6 @@ def log_add(a: torch.Tensor, b: torch.Tensor, stream=None) -> torch.Tensor:
 
 def stats_dict(stats: torch.Tensor) -> dict:
     vals = stats.cpu().tolist()
-    return dict(zip(STATS_FIELDS, vals))
+    out = dict(zip(STATS_FIELDS, vals))
+    out.update({f"clk{i}": v for i, v in enumerate(vals[len(STATS_FIELDS):])})
+    return out

@@ -27,8 +27,14 @@ def build(verbose: bool = False, out: str = LIB_PATH, defines=()) -> str:
     if verbose:
         print(" ".join(cmd))
     subprocess.run(cmd, check=True)
-    return LIB_PATH
+    return out
 
 
 if __name__ == "__main__":
-    print(build(verbose=True))
+    import argparse
+    ap = argparse.ArgumentParser(description=__doc__)
+    ap.add_argument("--define", action="append", default=[],
+                    help="preprocessor define, e.g. FLTOP_PHASE_CLOCKS for the profiling build")
+    ap.add_argument("--out", default=LIB_PATH, help="path of the shared library to write")
+    cli = ap.parse_args()
+    print(build(verbose=True, out=cli.out, defines=cli.define))

@@ -10,6 +10,8 @@ int check_shapes(int32_t B, int32_t T, int32_t V, int32_t beam) {
     if (B < 1 || T < 1 || V < 2) return FLTOP_ERR_BAD_SHAPE;
     if (V > FLTOP_MAX_VOCAB) return FLTOP_ERR_VOCAB_TOO_BIG;
     if (beam < 1 || beam > FLTOP_MAX_BEAM) return FLTOP_ERR_BAD_BEAM;
+    // trie node ids (1 + frame * beam + slot) are 32-bit
+    if ((int64_t)T * beam + 1 > (int64_t)INT32_MAX) return FLTOP_ERR_BAD_SHAPE;
     return FLTOP_OK;
 }
 
@@ -231,7 +233,7 @@ extern "C" const char* fltop_status_string(int status) {
     switch (status) {
         case FLTOP_OK: return "ok";
         case FLTOP_ERR_NULL_POINTER: return "a required pointer is NULL";
-        case FLTOP_ERR_BAD_SHAPE: return "bad shape: need B >= 1, T >= 1, V >= 2";
+        case FLTOP_ERR_BAD_SHAPE: return "bad shape: need B >= 1, T >= 1, V >= 2, T * beam < 2^31";
         case FLTOP_ERR_BAD_BEAM: return "beam outside 1..FLTOP_MAX_BEAM";
         case FLTOP_ERR_BAD_THRESHOLD: return "rel_threshold outside [0,1]";
         case FLTOP_ERR_WORKSPACE: return "workspace too small";

@@ -24,11 +24,12 @@
 //  - frame headers (which carry the first six survivors) are staged through LDS
 //    32 frames at a time, one chunk ahead, and barriers wait for LDS traffic only,
 //    so global loads and trie stores stay in flight across them;
-//  - frames whose only survivor is blank change no prefix and no order: their
-//    log-prob goes into one per-utterance offset (scores in LDS are relative to
-//    it) and a flag says that p_b = total, p_nb = -inf holds for every entry;
-//    such a frame touches neither the beam nor a barrier, and a run of them is
-//    consumed at once (the frames of a chunk are classified together);
+//  - frames whose only survivor is blank change no prefix and no order: every entry's
+//    total takes the frame's log-prob (the thread that owns the entry adds it in a
+//    register, in the order a plain implementation adds them) and a flag says that
+//    p_b = total, p_nb = -inf holds for every entry; a run of such frames is consumed at
+//    once (the frames of a chunk are classified together) and costs one LDS round trip
+//    and one barrier for the whole run;
 //  - frames with at most six survivors keep them in registers; what the prune
 //    stage can say about a frame by itself (blank kept?, the division constant
 //    that maps a candidate index to its beam entry) comes with the header;
@@ -100,7 +101,7 @@ struct StreamState {
     int32_t n_live;
     int32_t collapsed;
     int32_t out_len;      // length of the transcript as last written
-    double bias, kmax, kmin;
+    double kmax, kmin;
     // where the transcript and its entry frames were last written: the record of trie nodes
     // behind the written tokens holds for those rows only
     uint64_t out_tokens_at, out_frames_at;
@@ -314,12 +315,14 @@ __host__ __device__ inline size_t lm_lds_offset(int V, bool with_s_lp) {
     return s_lp_lds_offset(V) + (with_s_lp ? ((size_t)V * sizeof(float) + 15) / 16 * 16 : 0);
 }
 
-// Optional per-phase cycle accounting (thread 0 of every workgroup), compiled in only
-// with -DFLTOP_PHASE_CLOCKS; the default build carries none of it.
+// Optional per-phase cycle accounting, compiled in only with -DFLTOP_PHASE_CLOCKS; the default
+// build carries none of it.  The wavefronts of a workgroup form four groups (group 0 holds the
+// stay candidates, group 2 the first extension candidates); lane 0 of each group's first
+// wavefront keeps the clocks, so the table shows which group a barrier waits for.
 #ifdef FLTOP_PHASE_CLOCKS
 #define PHASE_MARK(idx)                      \
     do {                                     \
-        if (tid == 0) {                      \
+        if (ph_rec) {                        \
             const uint64_t now_ = clock64(); \
             ph_clk[idx] += now_ - ph_last;   \
             ph_last = now_;                  \
@@ -869,9 +872,8 @@ void beam_kernel(BeamArgs a) {
     int ext_i = 0, ext_g = 0, ext_G = 1;
     int gen = 0;         // beam generation: slab[gen], links[gen]
     int n_live = 1;
-    double bias = 0.0;       // log-mass of the blank-only frames, common to every entry
     bool collapsed = false;  // blank-only frames since the beam was last written
-    double kmax_v = 0.0, kmin_v = 0.0;  // bounds of the best / worst score (without bias)
+    double kmax_v = 0.0, kmin_v = 0.0;  // bounds of the best / worst score
     int prev_out_len = 0;       // streaming: length of the transcript the last call wrote ...
     uint64_t prev_tokens_at = 0, prev_frames_at = 0;  // ... and the rows it wrote it to
     if (carried) {
@@ -879,7 +881,6 @@ void beam_kernel(BeamArgs a) {
         prev_tokens_at = carried->out_tokens_at;
         prev_frames_at = carried->out_frames_at;
         n_live = carried->n_live;
-        bias = carried->bias;
         collapsed = carried->collapsed != 0;
         kmax_v = carried->kmax;
         kmin_v = carried->kmin;
@@ -889,6 +890,9 @@ void beam_kernel(BeamArgs a) {
     uint64_t st_surv = 0, st_cand = 0, st_peak = 0, st_beam = 0, st_pass = 0, st_exact = 0,
              st_drop = 0;
 #ifdef FLTOP_PHASE_CLOCKS
+    constexpr int kWavesPerGroup = kThreads / kWave >= 4 ? kThreads / kWave / 4 : 1;
+    const int ph_grp = (tid / kWave) / kWavesPerGroup;
+    const bool ph_rec = lane == 0 && (tid / kWave) % kWavesPerGroup == 0;
     uint64_t ph_clk[16] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
     uint64_t ph_last = clock64();
 #endif
@@ -926,13 +930,22 @@ void beam_kernel(BeamArgs a) {
             if (a.frame_beam && tid < t_end - t) a.frame_beam[trace_base + t + tid] = 0;
             break;
         }
-        // ---- run of blank-only frames: their log-probs go into the common offset, one by
-        //      one in frame order (so the sum does not depend on where chunks begin) --------
+        // ---- run of blank-only frames --------------------------------------------------
         const int run = __builtin_ctz(~(blank_only >> l) | 0x80000000u);
         if (run > 0) {
-            for (int k = 0; k < run; ++k)
-                bias += (double)__int_as_float(__builtin_amdgcn_readlane(lp_bits, l + k));
+            // every entry's total takes the run's log-probs one by one, in frame order, as a
+            // plain implementation adds them (the owner thread keeps the sum in a register)
+            BeamSlab<MB>* const cur_run = &slab[gen];
+            double own = tid < n_live ? cur_run->ptot[tid] : 0.0;
+            for (int k = 0; k < run; ++k) {
+                const double x = (double)__int_as_float(__builtin_amdgcn_readlane(lp_bits, l + k));
+                own += x;
+                kmax_v += x;
+                kmin_v += x;
+            }
+            if (tid < n_live) cur_run->ptot[tid] = own;
             collapsed = true;
+            lds_barrier();  // the new totals are read by other threads in the next full frame
             if (tid == 0) {
                 st_cand += (uint64_t)n_live * (uint64_t)run;
                 if ((uint64_t)n_live > st_peak) st_peak = (uint64_t)n_live;
@@ -1460,7 +1473,7 @@ void beam_kernel(BeamArgs a) {
             a.out_scores[b] = -INFINITY;
         } else {
             a.out_lengths[b] = fin.plen[best];
-            a.out_scores[b] = (float)(fin.ptot[best] + bias);
+            a.out_scores[b] = (float)fin.ptot[best];
         }
         if (a.stats) {
             atomicAdd((unsigned long long*)&a.stats->frames, (unsigned long long)len);
@@ -1471,13 +1484,14 @@ void beam_kernel(BeamArgs a) {
             atomicAdd((unsigned long long*)&a.stats->select_passes, (unsigned long long)st_pass);
             atomicAdd((unsigned long long*)&a.stats->exact_rankings, (unsigned long long)st_exact);
             atomicAdd((unsigned long long*)&a.stats->overflow_drops, (unsigned long long)st_drop);
-#ifdef FLTOP_PHASE_CLOCKS
-            for (int i = 0; i < 16; ++i)
-                atomicAdd((unsigned long long*)&a.stats->phase_clocks[i],
-                          (unsigned long long)ph_clk[i]);
-#endif
         }
     }
+#ifdef FLTOP_PHASE_CLOCKS
+    if (ph_rec && a.stats)
+        for (int i = 0; i < 16; ++i)
+            atomicAdd((unsigned long long*)&a.stats->phase_clocks[ph_grp * 16 + i],
+                      (unsigned long long)ph_clk[i]);
+#endif
     // Back-walk: thread 0 follows the every-8th-level links and records way-points; then
     // one thread per way-point walks the (at most 8) parents down to the next way-point.
     // A streaming decode remembers the trie node behind every token it wrote: where the walk
@@ -1555,8 +1569,8 @@ void beam_kernel(BeamArgs a) {
             const int64_t row = (int64_t)b * beam + rank;
             const int n = fin.plen[tid];
             a.nbest_lengths[row] = n;
-            a.nbest_pb[row] = (collapsed ? fin.ptot[tid] : fin.pb[tid]) + bias;
-            a.nbest_pnb[row] = collapsed ? -INFINITY : fin.pnb[tid] + bias;
+            a.nbest_pb[row] = collapsed ? fin.ptot[tid] : fin.pb[tid];
+            a.nbest_pnb[row] = collapsed ? -INFINITY : fin.pnb[tid];
             int node = fin.node[tid];
             int32_t* dst = a.nbest_tokens + row * a.out_stride;
             for (int p = n - 1; p >= 0 && node > 0 && (int64_t)node < a.trie_stride; --p) {
@@ -1582,7 +1596,6 @@ void beam_kernel(BeamArgs a) {
             carried->out_frames_at = (uint64_t)(uintptr_t)born_row;
             carried->n_live = n_live;
             carried->collapsed = collapsed ? 1 : 0;
-            carried->bias = bias;
             carried->kmax = kmax_v;
             carried->kmin = kmin_v;
         }

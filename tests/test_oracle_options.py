@@ -339,3 +339,25 @@ def test_token_frames_keep_the_first_entry_while_the_prefix_stays_in_the_beam(or
     k = len(toks[0])
     assert k >= 3 and toks[0] == [1] * k
     assert st["token_frames"][0] == [2 * j for j in range(k)]
+
+
+# --------------------------------------------------------------------------- structural ties
+def test_quantised_emissions_make_exact_score_ties(oracle_lib):
+    """Emissions on a grid of 1/2 make different prefixes score the same: the five best final
+    prefixes of this seeded utterance are bit-equal in the oracle, its choice among them is the
+    hash order, and the margin it reports is 0 (tests/test_gpu_ties.py says what the GPU path
+    owes on such inputs)."""
+    lp = synth.random_emissions(22191, 300, 13, 5, flat=1.0)
+    lp = (np.round(lp * 2) / 2).astype(np.float32)[215, :12]
+    final = oracle_lib.decode_beam(lp, 128, 1.0, top_n=20, max_entries=128)
+    totals = [float(np.logaddexp(pb, pnb)) for _, pb, pnb in final]
+    assert len(totals) >= 5 and len(set(totals[:5])) == 1
+    hashes = [oracle_lib.prefix_hash(tok) for tok, _, _ in final[:5]]
+    assert hashes == sorted(hashes)
+    toks, sc, st = oracle_lib.decode(lp[None], np.array([12], np.int32), 128, 1.0, top_n=20)
+    assert tuple(toks[0]) == final[0][0] and st["min_decision_margin"] == 0.0
+    # and a workload with continuous emissions has none
+    w = synth.WORKLOADS["cfg2_batch64"]
+    lp2, ln2 = synth.make_emissions(w, utterances=range(4))
+    st2 = oracle_lib.decode(lp2, ln2, w.beam, 0.01, n_threads=4)[2]
+    assert st2["min_decision_margin"] > 1e-9 and min(st2["margins"]) > 1e-9

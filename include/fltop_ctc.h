@@ -62,6 +62,8 @@ extern "C" {
 #define FLTOP_ERR_HIP            -7  /* a HIP call or kernel launch failed                  */
 #define FLTOP_ERR_ALIGNMENT      -8  /* workspace not 256-byte aligned                      */
 #define FLTOP_ERR_BAD_OPTION     -9  /* top_n < 0, or beam_threshold NaN                    */
+#define FLTOP_ERR_STATIC_SCRATCH -10 /* fltop_ctc_decode_static: the shapes need more than
+                                        FLTOP_STATIC_SCRATCH_BYTES of workspace             */
 
 #define FLTOP_MAX_BEAM   512
 #define FLTOP_MAX_VOCAB  4096
@@ -140,6 +142,22 @@ int fltop_ctc_decode(const float* logprobs, const int32_t* lengths,
                      void* workspace, size_t workspace_bytes,
                      int32_t* out_tokens, int32_t* out_lengths, float* out_scores,
                      fltop_stats* stats, void* hip_stream);
+
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid it): fltop_ctc_decode without the workspace arguments.  The
+ * survivor lists and the prefix trie go into an array of FLTOP_STATIC_SCRATCH_BYTES that is
+ * part of the library's device image (every GPU the library runs on holds its own copy until
+ * the process ends); the call allocates and frees nothing.  Inputs, outputs, argument rules
+ * and results are those of fltop_ctc_decode.  Shapes for which fltop_ctc_workspace_bytes()
+ * exceeds FLTOP_STATIC_SCRATCH_BYTES are refused with FLTOP_ERR_STATIC_SCRATCH before anything
+ * is enqueued.  All calls on one GPU share the one array, whatever their stream: calls that
+ * overlap in time on one GPU race, so order them (one stream, or events).  Nothing in the
+ * array has to be cleared between calls: each call writes what it later reads. */
+#define FLTOP_STATIC_SCRATCH_BYTES (64u << 20)
+int fltop_ctc_decode_static(const float* logprobs, const int32_t* lengths,
+                            int32_t B, int32_t T, int32_t V, const fltop_params* params,
+                            int32_t* out_tokens, int32_t* out_lengths, float* out_scores,
+                            fltop_stats* stats, void* hip_stream);
 
 /* The first stage alone (Algorithm 1's top-emission lookup and relative-
  * threshold test, which do not depend on the hypotheses, for every valid frame

@@ -18,7 +18,10 @@ LIB_PATH = os.environ.get("FLTOP_CTC_LIB") or os.path.join(_PKG, "libfltop_ctc.s
 MAX_BEAM = 512
 MAX_VOCAB = 4096
 
-EXPORTS = ("fltop_ctc_workspace_bytes", "fltop_ctc_decode", "fltop_ctc_prune", "fltop_ctc_search",
+STATIC_SCRATCH_BYTES = 64 << 20
+
+EXPORTS = ("fltop_ctc_workspace_bytes", "fltop_ctc_decode", "fltop_ctc_decode_static",
+           "fltop_ctc_prune", "fltop_ctc_search",
            "fltop_ctc_unpack_survivors", "fltop_ctc_token_ranks", "fltop_ctc_stream_state_bytes",
            "fltop_ctc_stream_begin", "fltop_ctc_stream_decode", "fltop_ctc_log_add",
            "fltop_status_string")
@@ -74,6 +77,9 @@ def load():
     lib.fltop_ctc_decode.restype = ctypes.c_int
     lib.fltop_ctc_decode.argtypes = [vp, vp, i32, i32, i32, ctypes.POINTER(FltopParams), vp, sz,
                                      vp, vp, vp, vp, vp]
+    lib.fltop_ctc_decode_static.restype = ctypes.c_int
+    lib.fltop_ctc_decode_static.argtypes = [vp, vp, i32, i32, i32, ctypes.POINTER(FltopParams),
+                                            vp, vp, vp, vp, vp]
     lib.fltop_ctc_search.restype = ctypes.c_int
     lib.fltop_ctc_search.argtypes = [vp, i32, i32, i32, ctypes.POINTER(FltopParams), vp, sz,
                                      vp, vp, vp, vp, vp]
@@ -142,6 +148,16 @@ def decode_raw(logprobs, lengths, params: FltopParams, workspace, workspace_nbyt
                                        ctypes.byref(params), _ptr(workspace), workspace_nbytes,
                                        _ptr(out_tokens), _ptr(out_lengths), _ptr(out_scores),
                                        _ptr(stats), _stream_handle(stream)))
+
+
+def decode_static_raw(logprobs, lengths, params: FltopParams, out_tokens, out_lengths, out_scores,
+                      stats, stream=None) -> int:
+    """Direct call of fltop_ctc_decode_static (workspace inside the library); returns the status."""
+    B, T, V = logprobs.shape
+    return int(load().fltop_ctc_decode_static(_ptr(logprobs), _ptr(lengths), B, T, V,
+                                              ctypes.byref(params), _ptr(out_tokens),
+                                              _ptr(out_lengths), _ptr(out_scores), _ptr(stats),
+                                              _stream_handle(stream)))
 
 
 def search_raw(lengths, shape, params: FltopParams, workspace, workspace_nbytes, out_tokens,

@@ -1,6 +1,7 @@
 // C ABI of the FLToP CTC decoder: argument checks, workspace carve-up, launches.
 // See include/fltop_ctc.h for the contract of every entry point.
 #include <cmath>
+#include <mutex>
 
 #include "fltop_internal.h"
 
@@ -155,6 +156,59 @@ extern "C" int fltop_ctc_decode(const float* logprobs, const int32_t* lengths, i
                           out_scores, stats, stream);
 }
 
+// ---- decode for callers that cannot allocate -------------------------------------------
+// The workspace of fltop_ctc_decode_static: one array in the library's own device image,
+// which every GPU the library runs on holds at its own address until the process ends.
+// `scratch` itself is only the host-side handle of that array; the device address is asked
+// for once per device (fetch_scratch) and only that address is ever handed to a kernel.
+static __device__ __align__(256) unsigned char scratch[FLTOP_STATIC_SCRATCH_BYTES];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_lock;
+void* g_scratch_at[kMaxDevices] = {};  // device address of `scratch`, per device
+
+// Device address of `scratch` on the current device, or nullptr with *err set.
+void* fetch_scratch(hipError_t* err) {
+    int dev = 0;
+    *err = hipGetDevice(&dev);
+    if (*err != hipSuccess) return nullptr;
+    if (dev < 0 || dev >= kMaxDevices) {
+        *err = hipErrorInvalidDevice;
+        return nullptr;
+    }
+    std::lock_guard<std::mutex> hold(g_scratch_lock);
+    if (!g_scratch_at[dev]) {
+        void* at = nullptr;
+        *err = hipGetSymbolAddress(&at, HIP_SYMBOL(scratch));
+        if (*err != hipSuccess || !at) {
+            if (*err == hipSuccess) *err = hipErrorInvalidSymbol;
+            return nullptr;
+        }
+        g_scratch_at[dev] = at;
+    }
+    return g_scratch_at[dev];
+}
+
+}  // namespace
+
+extern "C" int fltop_ctc_decode_static(const float* logprobs, const int32_t* lengths, int32_t B,
+                                       int32_t T, int32_t V, const fltop_params* params,
+                                       int32_t* out_tokens, int32_t* out_lengths,
+                                       float* out_scores, fltop_stats* stats, void* hip_stream) {
+    if (!params) return FLTOP_ERR_NULL_POINTER;
+    const size_t need = fltop_ctc_workspace_bytes(B, T, V, params->beam);
+    if (need > (size_t)FLTOP_STATIC_SCRATCH_BYTES) return FLTOP_ERR_STATIC_SCRATCH;
+    hipError_t e = hipSuccess;
+    void* at = fetch_scratch(&e);
+    if (!at) return FLTOP_ERR_HIP;
+    // need == 0 (bad shapes) falls through to the checks of the plain entry point
+    return fltop_ctc_decode(logprobs, lengths, B, T, V, params, at,
+                            (size_t)FLTOP_STATIC_SCRATCH_BYTES, out_tokens, out_lengths,
+                            out_scores, stats, hip_stream);
+}
+
 extern "C" size_t fltop_ctc_stream_state_bytes(int32_t B, int32_t T_total, int32_t beam) {
     if (check_shapes(B, T_total, 2, beam) != FLTOP_OK) return 0;
     return fltop::carve_stream(nullptr, B, T_total, beam).bytes;
@@ -241,6 +295,8 @@ extern "C" const char* fltop_status_string(int status) {
         case FLTOP_ERR_HIP: return "HIP launch failed";
         case FLTOP_ERR_ALIGNMENT: return "workspace not 256-byte aligned";
         case FLTOP_ERR_BAD_OPTION: return "top_n negative or beam_threshold NaN";
+        case FLTOP_ERR_STATIC_SCRATCH:
+            return "shapes need more workspace than FLTOP_STATIC_SCRATCH_BYTES";
         default: return "unknown status";
     }
 }

@@ -39,16 +39,18 @@ def test_header_constants_match_binding():
     assert int(re.search(r"#define FLTOP_MAX_VOCAB\s+(\d+)", text).group(1)) == binding.MAX_VOCAB
     codes = dict(re.findall(r"#define (FLTOP_(?:OK|ERR_[A-Z_]+))\s+(-?\d+)", text))
     assert codes["FLTOP_OK"] == "0"
-    assert sorted(int(v) for v in codes.values()) == list(range(-9, 1))
+    assert sorted(int(v) for v in codes.values()) == list(range(-10, 1))
+    assert int(re.search(r"#define FLTOP_STATIC_SCRATCH_BYTES\s+\((\d+)u << 20\)", text).group(1)) << 20 \
+        == binding.STATIC_SCRATCH_BYTES
 
 
 def test_status_strings(lib):
     seen = set()
-    for code in range(-9, 1):
+    for code in range(-10, 1):
         s = binding.status_string(code)
         assert s and s != "unknown status"
         seen.add(s)
-    assert len(seen) == 10
+    assert len(seen) == 11
     assert binding.status_string(-99) == "unknown status"
 
 
@@ -119,6 +121,16 @@ def test_argument_errors_are_reported_before_any_launch(lib):
         q.rel_threshold = 0.5
         setattr(q, field, bad)
         assert call(params=q) == -9
+    # the entry point with the workspace inside the library: shapes beyond it, and a missing
+    # params block, are refused before anything touches the GPU
+    big = binding.FltopParams()
+    big.beam = 100
+    big.rel_threshold = 0.01
+    assert binding.workspace_bytes(256, 1500, 32, 100) > binding.STATIC_SCRATCH_BYTES
+    assert lib.fltop_ctc_decode_static(fake, fake, 256, 1500, 32, ctypes.byref(big), fake, fake,
+                                       fake, None, None) == -10
+    assert lib.fltop_ctc_decode_static(fake, fake, 2, 10, 32, None, fake, fake, fake, None,
+                                       None) == -1
     assert lib.fltop_ctc_token_ranks(None, 2, 10, 32, fake, fake, fake, None, None, None,
                                      None) == -1
     assert lib.fltop_ctc_token_ranks(fake, 2, 10, 1, fake, fake, fake, None, None, None,

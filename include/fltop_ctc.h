@@ -55,7 +55,8 @@ extern "C" {
 #define FLTOP_OK                  0
 #define FLTOP_ERR_NULL_POINTER   -1  /* a required pointer is NULL                          */
 #define FLTOP_ERR_BAD_SHAPE      -2  /* B < 1, T < 1, V < 2, or T * beam >= 2^31            */
-#define FLTOP_ERR_BAD_BEAM       -3  /* beam < 1 or beam > FLTOP_MAX_BEAM                   */
+#define FLTOP_ERR_BAD_BEAM       -3  /* beam < 1 or > FLTOP_MAX_BEAM; or beam > 512 together
+                                        with V > FLTOP_MAX_VOCAB_WIDE_BEAM or with streaming */
 #define FLTOP_ERR_BAD_THRESHOLD  -4  /* rel_threshold outside [0, 1] or NaN                 */
 #define FLTOP_ERR_WORKSPACE      -5  /* workspace smaller than fltop_ctc_workspace_bytes()  */
 #define FLTOP_ERR_VOCAB_TOO_BIG  -6  /* V > FLTOP_MAX_VOCAB                                 */
@@ -65,8 +66,12 @@ extern "C" {
 #define FLTOP_ERR_STATIC_SCRATCH -10 /* fltop_ctc_decode_static: the shapes need more than
                                         FLTOP_STATIC_SCRATCH_BYTES of workspace             */
 
-#define FLTOP_MAX_BEAM   512
+#define FLTOP_MAX_BEAM   1024  /* the paper's decoder runs beam-size 1000 (Sec. 4)            */
 #define FLTOP_MAX_VOCAB  4096
+/* A beam of more than 512 entries fills the compute unit's local memory: such a decode takes
+ * vocabularies up to FLTOP_MAX_VOCAB_WIDE_BEAM only, and the streaming entry points take beams
+ * up to 512. */
+#define FLTOP_MAX_VOCAB_WIDE_BEAM 2048
 
 /* Decoder settings (host POD, read during the call only; zero-initialise it, then set
  * what is needed).  Algorithm 1's arguments: beam_size -> beam, R -> rel_threshold,

@@ -15,7 +15,9 @@ import torch
 _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("FLTOP_CTC_LIB") or os.path.join(_PKG, "libfltop_ctc.so")
 
-MAX_BEAM = 512
+MAX_BEAM = 1024
+MAX_BEAM_STREAMING = 512      # the streaming entry points
+MAX_VOCAB_WIDE_BEAM = 2048    # vocabulary limit of decodes with beam > 512
 MAX_VOCAB = 4096
 
 STATIC_SCRATCH_BYTES = 64 << 20

@@ -11,6 +11,7 @@ int check_shapes(int32_t B, int32_t T, int32_t V, int32_t beam) {
     if (B < 1 || T < 1 || V < 2) return FLTOP_ERR_BAD_SHAPE;
     if (V > FLTOP_MAX_VOCAB) return FLTOP_ERR_VOCAB_TOO_BIG;
     if (beam < 1 || beam > FLTOP_MAX_BEAM) return FLTOP_ERR_BAD_BEAM;
+    if (beam > fltop::kBeamInLds && V > FLTOP_MAX_VOCAB_WIDE_BEAM) return FLTOP_ERR_BAD_BEAM;
     // trie node ids (1 + frame * beam + slot) are 32-bit
     if ((int64_t)T * beam + 1 > (int64_t)INT32_MAX) return FLTOP_ERR_BAD_SHAPE;
     return FLTOP_OK;
@@ -210,7 +211,7 @@ extern "C" int fltop_ctc_decode_static(const float* logprobs, const int32_t* len
 }
 
 extern "C" size_t fltop_ctc_stream_state_bytes(int32_t B, int32_t T_total, int32_t beam) {
-    if (check_shapes(B, T_total, 2, beam) != FLTOP_OK) return 0;
+    if (check_shapes(B, T_total, 2, beam) != FLTOP_OK || beam > fltop::kBeamInLds) return 0;
     return fltop::carve_stream(nullptr, B, T_total, beam).bytes;
 }
 
@@ -218,6 +219,7 @@ extern "C" int fltop_ctc_stream_begin(void* state, size_t state_bytes, int32_t B
                                       int32_t beam, void* hip_stream) {
     int rc = check_shapes(B, T_total, 2, beam);
     if (rc != FLTOP_OK) return rc;
+    if (beam > fltop::kBeamInLds) return FLTOP_ERR_BAD_BEAM;  // the carried record is laid out for 512
     rc = check_workspace(state, state_bytes, fltop_ctc_stream_state_bytes(B, T_total, beam));
     if (rc != FLTOP_OK) return rc;
     const fltop::StreamSpace sp = fltop::carve_stream(state, B, T_total, beam);
@@ -236,6 +238,7 @@ extern "C" int fltop_ctc_stream_decode(const float* logprobs, const int32_t* len
         return FLTOP_ERR_NULL_POINTER;
     int rc = check_shapes(B, T_chunk, V, params->beam);
     if (rc != FLTOP_OK) return rc;
+    if (params->beam > fltop::kBeamInLds) return FLTOP_ERR_BAD_BEAM;
     if (T_total < T_chunk) return FLTOP_ERR_BAD_SHAPE;
     rc = check_threshold(params->rel_threshold);
     if (rc != FLTOP_OK) return rc;
@@ -288,7 +291,8 @@ extern "C" const char* fltop_status_string(int status) {
         case FLTOP_OK: return "ok";
         case FLTOP_ERR_NULL_POINTER: return "a required pointer is NULL";
         case FLTOP_ERR_BAD_SHAPE: return "bad shape: need B >= 1, T >= 1, V >= 2, T * beam < 2^31";
-        case FLTOP_ERR_BAD_BEAM: return "beam outside 1..FLTOP_MAX_BEAM";
+        case FLTOP_ERR_BAD_BEAM:
+            return "beam outside 1..FLTOP_MAX_BEAM (or above 512 with V > 2048 or with streaming)";
         case FLTOP_ERR_BAD_THRESHOLD: return "rel_threshold outside [0,1]";
         case FLTOP_ERR_WORKSPACE: return "workspace too small";
         case FLTOP_ERR_VOCAB_TOO_BIG: return "V exceeds FLTOP_MAX_VOCAB";

@@ -49,14 +49,16 @@ namespace {
 
 constexpr int kThreadsSmall = 256;  // workgroup size for small vocabularies
 constexpr int kThreadsLarge = 512;  // and for large ones (see launch_beam)
+constexpr int kThreadsHuge = 1024;  // beams beyond 512 entries: still one thread per entry
 constexpr int kThreadsDense = 128;  // small frames, batches larger than the chip holds at once
 constexpr int kWave = 64;
 // The beam lives in LDS, so its capacity is a compile-time size: kernels are built for a
 // small one (which keeps several workgroups per CU for large batches) and for the largest.
 constexpr int kBeamSmall = 128;
 constexpr int kBeamTiny = 64;  // one-shot decodes of dense batches (17 KB of LDS)
-constexpr int kBeamLarge = FLTOP_MAX_BEAM;
-static_assert(kBeamLarge == 512, "the LDS budget below is worked out for 512 entries");
+constexpr int kBeamLarge = 512;
+constexpr int kBeamHuge = FLTOP_MAX_BEAM;  // 1000-entry beams (paper Sec. 4: beam-size 1000)
+static_assert(kBeamHuge == 1024, "the LDS budget below is worked out for 1024 entries");
 constexpr int kFine = 1024;  // histogram bins
 constexpr int kCoarse = 64;  // one per lane; a coarse bin covers 16 fine bins
 constexpr int kExactCap = 64;
@@ -68,28 +70,90 @@ constexpr int kWaypoints = 256;
 constexpr uint64_t kGolden = 0x9E3779B97F4A7C15ull;
 constexpr uint64_t kAllOnes = ~0ull;
 
+// Two generations of a 1024-entry beam with everything in LDS would take 219 KB of the 160 KB
+// a workgroup can have.  For that capacity the fields that only the trie bookkeeping needs
+// (parent hash, trie node, length, skip ancestor: read once per emitted entry, never by the
+// candidate evaluation) live in global memory instead (ColdSlab, in the workspace; L2-resident),
+// the children lists are left out (builds with 512 threads and more use the pair table) and the
+// two open-addressing tables are half as large per entry.
+template <int MB>
+struct SlabTraits {
+    static constexpr bool kColdGlobal = MB > 512;
+    static constexpr int kColdInLds = kColdGlobal ? 1 : MB;   // places of the cold fields in LDS
+    static constexpr int kKidLists = kColdGlobal ? 4 : MB;    // places of the children lists
+    static constexpr int kHashSlots = kColdGlobal ? 2 * MB : 4 * MB;
+};
+
 template <int MB>
 struct BeamSlab {
     uint64_t h[MB];   // prefix hash
-    uint64_t hp[MB];  // parent prefix hash (unused when plen == 0)
+    uint64_t hp[SlabTraits<MB>::kColdInLds];  // parent prefix hash (unused when plen == 0)
     double pb[MB];
     double pnb[MB];
     double ptot[MB];
     int32_t last[MB];  // last token, -1 for the empty prefix
-    int32_t node[MB];  // trie node of the prefix
-    int32_t plen[MB];  // prefix length
-    int32_t xanc[MB];  // trie node of the ancestor at depth 8*floor(plen/8)
+    int32_t node[SlabTraits<MB>::kColdInLds];  // trie node of the prefix
+    int32_t plen[SlabTraits<MB>::kColdInLds];  // prefix length
+    int32_t xanc[SlabTraits<MB>::kColdInLds];  // trie node of the ancestor at depth 8*floor(plen/8)
+};
+
+// The same four fields of one beam generation in global memory (kColdGlobal builds).
+template <int MB>
+struct ColdSlab {
+    uint64_t hp[MB];
+    int32_t node[MB];
+    int32_t plen[MB];
+    int32_t xanc[MB];
+};
+static_assert(sizeof(ColdSlab<FLTOP_MAX_BEAM>) == kColdBytesPerGeneration,
+              "the workspace reserves two of these per utterance");
+
+// One generation's trie bookkeeping fields, wherever they live.
+template <int MB>
+struct ColdRef {
+    BeamSlab<MB>* lds;
+    ColdSlab<MB>* glb;
+    __device__ __forceinline__ uint64_t hp(int i) const {
+        if constexpr (SlabTraits<MB>::kColdGlobal) return glb->hp[i];
+        else return lds->hp[i];
+    }
+    __device__ __forceinline__ int32_t node(int i) const {
+        if constexpr (SlabTraits<MB>::kColdGlobal) return glb->node[i];
+        else return lds->node[i];
+    }
+    __device__ __forceinline__ int32_t plen(int i) const {
+        if constexpr (SlabTraits<MB>::kColdGlobal) return glb->plen[i];
+        else return lds->plen[i];
+    }
+    __device__ __forceinline__ int32_t xanc(int i) const {
+        if constexpr (SlabTraits<MB>::kColdGlobal) return glb->xanc[i];
+        else return lds->xanc[i];
+    }
+    __device__ __forceinline__ void set(int i, uint64_t hp_, int32_t node_, int32_t plen_,
+                                        int32_t xanc_) const {
+        if constexpr (SlabTraits<MB>::kColdGlobal) {
+            glb->hp[i] = hp_;
+            glb->node[i] = node_;
+            glb->plen[i] = plen_;
+            glb->xanc[i] = xanc_;
+        } else {
+            lds->hp[i] = hp_;
+            lds->node[i] = node_;
+            lds->plen[i] = plen_;
+            lds->xanc[i] = xanc_;
+        }
+    }
 };
 
 // parent / children links of one beam generation
 template <int MB>
 struct alignas(16) Links {
     int32_t par[MB];
-    int32_t first_kid[MB];
-    int32_t next_kid[MB];
+    int32_t first_kid[SlabTraits<MB>::kKidLists];
+    int32_t next_kid[SlabTraits<MB>::kKidLists];
     uint32_t kidmask[MB];  // bit (token & 31) set for every child in the beam
-    int32_t ht[4 * MB];      // open addressing: slot -> beam index of a prefix that entered
-                                 // in this generation's frame, keyed by prefix hash
+    int32_t ht[SlabTraits<MB>::kHashSlots];  // open addressing: slot -> beam index of a prefix that
+                                             // entered in this generation's frame, keyed by prefix hash
 };
 
 // What a streaming (chunked) decode carries from one call to the next, per utterance: the
@@ -115,7 +179,7 @@ static_assert(sizeof(StreamState<kBeamSmall>) % 8 == 0 && sizeof(StreamState<kBe
               "records sit in an array: doubles stay aligned");
 static_assert(offsetof(Links<kBeamSmall>, ht) == 4 * kBeamSmall * sizeof(int32_t) &&
                   offsetof(Links<kBeamLarge>, ht) == 4 * kBeamLarge * sizeof(int32_t),
-              "the four link arrays are the head of Links");
+              "the four link arrays are the head of Links (streaming copies them as one block)");
 
 struct BeamArgs {
     const int32_t* lengths;
@@ -123,6 +187,7 @@ struct BeamArgs {
     const Survivor* rec;
     TrieNode* trie;
     int64_t trie_stride;
+    void* cold;             // kColdGlobal builds: [B][2] ColdSlab, else unused
     const float* lm_table;  // global copy (always valid when LM is on)
     const float* lm_bound;
     double lm_alpha, lm_beta;
@@ -662,7 +727,7 @@ __device__ __forceinline__ bool is_selected(const FrameCtx<MB>& f, uint64_t selD
 
 template <int MB>
 __device__ __forceinline__ void publish_hash(Links<MB>* lkn, uint64_t hh, int slot) {
-    constexpr int kHashSlots = 4 * MB;
+    constexpr int kHashSlots = SlabTraits<MB>::kHashSlots;
     uint32_t hs = (uint32_t)hh & (kHashSlots - 1);
     for (int probe = 0; probe < kHashSlots; ++probe) {
         if (atomicCAS(&lkn->ht[hs], -1, slot) == -1) break;
@@ -673,6 +738,7 @@ __device__ __forceinline__ void publish_hash(Links<MB>* lkn, uint64_t hh, int sl
 // Entry `se` keeps its prefix: copy it into `slot` of the next beam with its new masses.
 template <int MB>
 __device__ __forceinline__ void emit_stay(const FrameCtx<MB>& f, BeamSlab<MB>* nxt, Links<MB>* lkn,
+                                          const ColdRef<MB>& ccur, const ColdRef<MB>& cnxt,
                                           int32_t* newslot, int slot, int beam, int se, double pb,
                                           double pnb, double tot) {
     if (slot >= beam) return;  // only after a hash collision
@@ -684,20 +750,18 @@ __device__ __forceinline__ void emit_stay(const FrameCtx<MB>& f, BeamSlab<MB>* n
     newslot[se] = slot;
     lkn->par[slot] = par_old >= 0 ? par_old : -2;
     nxt->h[slot] = hh;
-    nxt->hp[slot] = cur->hp[se];
     nxt->pb[slot] = pb;
     nxt->pnb[slot] = pnb;
     nxt->ptot[slot] = tot;
     nxt->last[slot] = cur->last[se];
-    nxt->node[slot] = cur->node[se];
-    nxt->plen[slot] = cur->plen[se];
-    nxt->xanc[slot] = cur->xanc[se];
+    cnxt.set(slot, ccur.hp(se), ccur.node(se), ccur.plen(se), ccur.xanc(se));
 }
 
 // Entry `se` extended by token `tk` becomes a new prefix in `slot`; its trie node id is
 // fixed by (frame, slot), so no counter is needed.
 template <int MB>
-__device__ __forceinline__ void emit_ext(const FrameCtx<MB>& f, BeamSlab<MB>* nxt, Links<MB>* lkn, int slot,
+__device__ __forceinline__ void emit_ext(const FrameCtx<MB>& f, BeamSlab<MB>* nxt, Links<MB>* lkn,
+                                         const ColdRef<MB>& ccur, const ColdRef<MB>& cnxt, int slot,
                                          int beam, int t, uint64_t D, int se, int32_t tk,
                                          uint64_t hh, bool have_h, TrieNode* trie,
                                          int64_t trie_stride) {
@@ -706,19 +770,16 @@ __device__ __forceinline__ void emit_ext(const FrameCtx<MB>& f, BeamSlab<MB>* nx
     if (!have_h) hh = cand_hash(f, se, tk);
     const double sc = key_value(f.Rk - D);
     const int node = 1 + t * beam + slot;
-    const int depth = cur->plen[se] + 1;
-    const int32_t xa = cur->xanc[se];
+    const int depth = ccur.plen(se) + 1;
+    const int32_t xa = ccur.xanc(se);
     nxt->h[slot] = hh;
-    nxt->hp[slot] = cur->h[se];
     nxt->pb[slot] = -INFINITY;
     nxt->pnb[slot] = sc;
     nxt->ptot[slot] = sc;
     nxt->last[slot] = tk;
-    nxt->node[slot] = node;
-    nxt->plen[slot] = depth;
-    nxt->xanc[slot] = (depth & 7) == 0 ? node : xa;
+    cnxt.set(slot, cur->h[se], node, depth, (depth & 7) == 0 ? node : xa);
     TrieNode tn;
-    tn.parent = cur->node[se];
+    tn.parent = ccur.node(se);
     tn.xup = xa;
     tn.tok = tk;
     tn.depth = depth;
@@ -738,11 +799,13 @@ void beam_kernel(BeamArgs a) {
     constexpr int kWalkers = kThreads < kWaypoints ? kThreads : kWaypoints;  // back-walk batch
     static_assert(THREADS >= 4 * kChunk, "a chunk of headers is staged 16 bytes per thread");
     constexpr int kMaxBeam = MB;
-    constexpr int kHashSlots = 4 * MB;
+    constexpr int kHashSlots = SlabTraits<MB>::kHashSlots;
+    constexpr bool kColdGlobal = SlabTraits<MB>::kColdGlobal;
     static_assert(THREADS >= MB, "one thread per beam entry");
-    // the 512-thread builds take a thread's candidates from one entry (see EntryView)
-    constexpr bool kEntryMajor = THREADS == kThreadsLarge;
-    constexpr int kKidSlots = kEntryMajor ? 4 * MB : 4;
+    // builds with 512 threads or more take a thread's candidates from one entry (see EntryView)
+    constexpr bool kEntryMajor = THREADS >= kThreadsLarge;
+    static_assert(kEntryMajor || !kColdGlobal, "the largest capacity has no children lists");
+    constexpr int kKidSlots = kEntryMajor ? (kColdGlobal ? 2 * MB : 4 * MB) : 4;
     __shared__ uint32_t kidset2[2][kKidSlots];  // (parent place, token) pairs, per generation
     __shared__ BeamSlab<MB> slab[2];
     __shared__ Links<MB> links[2];
@@ -777,6 +840,9 @@ void beam_kernel(BeamArgs a) {
 
     StreamState<MB>* const carried =
         a.stream ? static_cast<StreamState<MB>*>(a.stream) + b : nullptr;  // uniform
+    // kColdGlobal: this utterance's two generations of trie bookkeeping fields
+    ColdSlab<MB>* const cold_gen =
+        kColdGlobal ? static_cast<ColdSlab<MB>*>(a.cold) + 2 * (int64_t)b : nullptr;
     const int32_t t_base = carried ? carried->frames_done : 0;
     int32_t len = a.lengths[b];
     len = len < 0 ? 0 : (len > a.T ? a.T : len);
@@ -809,8 +875,10 @@ void beam_kernel(BeamArgs a) {
     for (int g2 = 0; g2 < 2; ++g2) {
         if (tid < kMaxBeam) {
             links[g2].par[tid] = -1;
-            links[g2].first_kid[tid] = -1;
-            links[g2].next_kid[tid] = -1;
+            if (!kColdGlobal) {
+                links[g2].first_kid[tid] = -1;
+                links[g2].next_kid[tid] = -1;
+            }
             links[g2].kidmask[tid] = 0u;
         }
         for (int i = tid; i < kHashSlots; i += kThreads) links[g2].ht[i] = -1;
@@ -833,14 +901,11 @@ void beam_kernel(BeamArgs a) {
     } else if (tid == 0) {
         BeamSlab<MB>& s0 = slab[0];
         s0.h[0] = kGolden;
-        s0.hp[0] = 0;
         s0.pb[0] = 0.0;
         s0.pnb[0] = -INFINITY;
         s0.ptot[0] = 0.0;
         s0.last[0] = -1;
-        s0.node[0] = 0;
-        s0.plen[0] = 0;
-        s0.xanc[0] = 0;
+        ColdRef<MB>{&slab[0], cold_gen}.set(0, 0, 0, 0, 0);
     }
     TrieNode* trie = a.trie + (int64_t)b * trie_stride;
     double lm_ub = 0.0;  // upper bound of any LM term (never below 0)
@@ -963,6 +1028,8 @@ void beam_kernel(BeamArgs a) {
         BeamSlab<MB>* const nxt = &slab[gen ^ 1];
         Links<MB>* const lk = &links[gen];
         Links<MB>* const lkn = &links[gen ^ 1];
+        const ColdRef<MB> ccur{cur, kColdGlobal ? cold_gen + gen : nullptr};
+        const ColdRef<MB> cnxt{nxt, kColdGlobal ? cold_gen + (gen ^ 1) : nullptr};
 
         // ---- survivors: registers for K <= 6, LDS staging beyond ------------------------
         const bool big = K > kRegK;
@@ -1327,10 +1394,11 @@ void beam_kernel(BeamArgs a) {
             }
             int slot = base + incl - cnt;
             PHASE_MARK(9);
-            if (sel_s) emit_stay(fc, nxt, lkn, newslot, slot++, beam, tid, my_pb, my_pnb, my_tot);
+            if (sel_s)
+                emit_stay(fc, nxt, lkn, ccur, cnxt, newslot, slot++, beam, tid, my_pb, my_pnb, my_tot);
             if (sel_0)
-                emit_ext(fc, nxt, lkn, slot++, beam, t_base + t, cD0, cI0, cT0, hh0, hv0, trie,
-                         trie_stride);
+                emit_ext(fc, nxt, lkn, ccur, cnxt, slot++, beam, t_base + t, cD0, cI0, cT0, hh0, hv0,
+                         trie, trie_stride);
         }
         for (int m = kRegCand; m < M; ++m) {  // candidates beyond the register cache
             int e, k;
@@ -1357,10 +1425,13 @@ void beam_kernel(BeamArgs a) {
             if (lane == 0) base = atomicAdd(&sh_nnew, __popcll(m_sel));
             base = __builtin_amdgcn_readfirstlane(base);
             if (sel)
-                emit_ext(fc, nxt, lkn, base + lanes_below(m_sel, lane), beam, t_base + t, D, se, tk,
-                         hh, have_h, trie, trie_stride);
+                emit_ext(fc, nxt, lkn, ccur, cnxt, base + lanes_below(m_sel, lane), beam, t_base + t,
+                         D, se, tk, hh, have_h, trie, trie_stride);
         }
-        lds_barrier();
+        // the links phase reads what other threads have just emitted: LDS always, and in
+        // kColdGlobal builds their stores to global memory too
+        if (kColdGlobal) __syncthreads();
+        else lds_barrier();
         PHASE_MARK(5);
 
         // ---- adopt the new beam; rebuild parent / children links ---------------------
@@ -1375,8 +1446,8 @@ void beam_kernel(BeamArgs a) {
             const int32_t code = lkn->par[tid];
             if (code >= 0) {
                 p = newslot[code];  // the parent was in the old beam: did it stay, and where
-            } else if (nxt->plen[tid] > 0) {
-                const uint64_t want = nxt->hp[tid];
+            } else if (cnxt.plen(tid) > 0) {
+                const uint64_t want = cnxt.hp(tid);
                 uint32_t hs = (uint32_t)want & (kHashSlots - 1);
                 for (int probe = 0; probe < kHashSlots; ++probe) {
                     const int v = lkn->ht[hs];
@@ -1411,7 +1482,7 @@ void beam_kernel(BeamArgs a) {
                 for (int i = u; i < kKidSlots / 4; i += kThreads / 2)
                     reinterpret_cast<int4*>(kidset2[gen])[i] = ones;
             for (int i = u; i < kMaxBeam / 4; i += kThreads / 2) {
-                reinterpret_cast<int4*>(lk->first_kid)[i] = ones;
+                if (!kColdGlobal) reinterpret_cast<int4*>(lk->first_kid)[i] = ones;
                 reinterpret_cast<int4*>(lk->kidmask)[i] = zeros;
             }
             for (int i = u; i < kFine / 4; i += kThreads / 2)
@@ -1447,6 +1518,7 @@ void beam_kernel(BeamArgs a) {
 
     // ---- best prefix (paper: GetHighestScorePrefix) ----------------------------------
     BeamSlab<MB>& fin = slab[gen];
+    const ColdRef<MB> cfin{&slab[gen], kColdGlobal ? cold_gen + gen : nullptr};
     int32_t* wp_node = reinterpret_cast<int32_t*>(hfine);  // the histogram is idle now
     int32_t* wp_depth = wp_node + kWaypoints;
     static_assert(2 * kWaypoints <= kFine, "way-points alias the histogram");
@@ -1472,7 +1544,7 @@ void beam_kernel(BeamArgs a) {
             a.out_lengths[b] = 0;
             a.out_scores[b] = -INFINITY;
         } else {
-            a.out_lengths[b] = fin.plen[best];
+            a.out_lengths[b] = cfin.plen(best);
             a.out_scores[b] = (float)fin.ptot[best];
         }
         if (a.stats) {
@@ -1503,9 +1575,9 @@ void beam_kernel(BeamArgs a) {
     int32_t* const wrote = a.out_nodes ? a.out_nodes + (int64_t)b * a.out_stride : nullptr;
     const bool same_rows = wrote && prev_tokens_at == (uint64_t)(uintptr_t)out_row &&
                            prev_frames_at == (uint64_t)(uintptr_t)born_row;
-    const int new_out_len = best >= 0 ? fin.plen[best] : 0;
+    const int new_out_len = best >= 0 ? cfin.plen(best) : 0;
     if (best >= 0) {
-        int node = fin.node[best];
+        int node = cfin.node(best);
         int depth = new_out_len;
         while (depth > 0) {  // uniform: node/depth are re-read from LDS after each batch
             if (tid == 0) {
@@ -1567,11 +1639,11 @@ void beam_kernel(BeamArgs a) {
                 rank += (oK > myK || (oK == myK && oH < myH)) ? 1 : 0;
             }
             const int64_t row = (int64_t)b * beam + rank;
-            const int n = fin.plen[tid];
+            const int n = cfin.plen(tid);
             a.nbest_lengths[row] = n;
             a.nbest_pb[row] = collapsed ? fin.ptot[tid] : fin.pb[tid];
             a.nbest_pnb[row] = collapsed ? -INFINITY : fin.pnb[tid];
-            int node = fin.node[tid];
+            int node = cfin.node(tid);
             int32_t* dst = a.nbest_tokens + row * a.out_stride;
             for (int p = n - 1; p >= 0 && node > 0 && (int64_t)node < a.trie_stride; --p) {
                 const TrieNode tn = trie[node];
@@ -1701,6 +1773,7 @@ hipError_t launch_beam(const int32_t* lengths, int32_t B, int32_t T, int32_t V,
     a.rec = ws.rec;
     a.trie = carried ? carried->trie : ws.trie;
     a.trie_stride = carried ? carried->trie_stride : ws.trie_stride;
+    a.cold = ws.cold;
     a.stream = carried ? carried->records : nullptr;
     a.out_nodes = carried ? carried->out_nodes : nullptr;
     a.t_total = carried ? carried->t_total : T;
@@ -1734,6 +1807,9 @@ hipError_t launch_beam(const int32_t* lengths, int32_t B, int32_t T, int32_t V,
     const bool wide =
         V > 64 || (p.rel_threshold == 0.0f && (int64_t)p.beam * kept_at_most >= 512);
     const bool large_beam = p.beam > kBeamSmall;
+    const bool huge_beam = p.beam > kBeamLarge;  // 1024-entry build, 1024 threads, one per CU
+    if (huge_beam && (carried != nullptr || V > FLTOP_MAX_VOCAB_WIDE_BEAM))
+        return hipErrorInvalidValue;  // the entry points refuse these before they get here
     int n_cu = 0;
     hipError_t qe = compute_units(&n_cu);
     if (qe != hipSuccess) return qe;
@@ -1751,7 +1827,8 @@ hipError_t launch_beam(const int32_t* lengths, int32_t B, int32_t T, int32_t V,
     // (two per SIMD) evaluate twice as fast (measured: V = 1024 27% faster per decode with 512
     // threads, V = 32 at r = 0.01 6% slower).
     // Beam capacity: up to 128 entries the beam state takes 30 KB of LDS; beyond, the
-    // 512-entry build (116 KB, one thread per entry, one workgroup per CU) is used.
+    // 512-entry build (116 KB, one thread per entry, one workgroup per CU) is used, and beyond
+    // that the 1024-entry build (1024 threads, 134 KB, part of the state in global memory).
     // Residency: at two wavefronts per SIMD a CU holds two 256-thread workgroups (one of 512
     // threads).  A batch with more utterances than that over the whole chip is bound by
     // instruction issue, not by one frame's latency, and small frames then run best as two
@@ -1779,7 +1856,10 @@ hipError_t launch_beam(const int32_t* lengths, int32_t B, int32_t T, int32_t V,
     }
 #define FLTOP_LAUNCH_BEAM(LM_)                                                               \
     do {                                                                                     \
-        if (large_beam)                                                                      \
+        if (huge_beam)                                                                       \
+            hipLaunchKernelGGL((beam_kernel<LM_, kThreadsHuge, kBeamHuge, 4>),               \
+                               dim3((unsigned)B), dim3(kThreadsHuge), dyn, stream, a);       \
+        else if (large_beam)                                                                 \
             hipLaunchKernelGGL((beam_kernel<LM_, kThreadsLarge, kBeamLarge, 2>),             \
                                dim3((unsigned)B), dim3(kThreadsLarge), dyn, stream, a);      \
         else if (wide && very_dense)                                                         \

@@ -56,11 +56,17 @@ __host__ __device__ inline int32_t lanes_per_frame(int32_t V) {
     return l;
 }
 
+// Beams beyond 512 entries keep four fields of every beam entry (parent hash, trie node,
+// length, skip ancestor: 20 bytes) in global memory, two generations per utterance.
+constexpr int32_t kBeamInLds = 512;
+constexpr size_t kColdBytesPerGeneration = (size_t)FLTOP_MAX_BEAM * 20;
+
 struct Workspace {
     FrameHdr* hdr;      // [B*T]
     Survivor* rec;      // [B*T][V]: survivors of rank >= 6 (slot = rank)
     TrieNode* trie;     // [B][trie_stride]
     float* lm_bound;    // [kLmBoundParts] partial maxima of lm_weight*table+bonus
+    void* cold;         // [B][2][kColdBytesPerGeneration] when beam > kBeamInLds, else unused
     int64_t trie_stride;
     size_t bytes;
 };
@@ -76,12 +82,15 @@ inline Workspace carve_workspace(void* base, int32_t B, int32_t T, int32_t V, in
     w.trie_stride = (int64_t)T * beam + 1;
     const size_t off_lmb =
         align_up(off_trie + (size_t)B * (size_t)w.trie_stride * sizeof(TrieNode), 256);
-    w.bytes = off_lmb + 256;
+    const size_t off_cold = off_lmb + 256;
+    w.bytes = off_cold + (beam > kBeamInLds ? align_up((size_t)B * 2 * kColdBytesPerGeneration, 256)
+                                            : 0);
     char* p = static_cast<char*>(base);
     w.hdr = p ? reinterpret_cast<FrameHdr*>(p + off_hdr) : nullptr;
     w.rec = p ? reinterpret_cast<Survivor*>(p + off_rec) : nullptr;
     w.trie = p ? reinterpret_cast<TrieNode*>(p + off_trie) : nullptr;
     w.lm_bound = p ? reinterpret_cast<float*>(p + off_lmb) : nullptr;
+    w.cold = p ? p + off_cold : nullptr;
     return w;
 }
 

@@ -100,6 +100,14 @@ def test_argument_errors_are_reported_before_any_launch(lib):
         q.beam = bad_beam
         q.rel_threshold = 0.01
         assert call(params=q) == -3
+    wide = binding.FltopParams()  # a beam beyond 512 entries takes vocabularies up to 2048 only
+    wide.beam = 600
+    wide.rel_threshold = 0.01
+    assert call(params=wide, V=binding.MAX_VOCAB_WIDE_BEAM + 1,
+                nbytes=1 << 40) == -3
+    assert binding.workspace_bytes(2, 10, binding.MAX_VOCAB_WIDE_BEAM + 1, 600) == 0
+    assert binding.workspace_bytes(2, 10, binding.MAX_VOCAB_WIDE_BEAM, 600) > \
+        binding.workspace_bytes(2, 10, binding.MAX_VOCAB_WIDE_BEAM, 512)
     for bad_r in (-0.1, 1.5, float("nan")):
         q = binding.FltopParams()
         q.beam = 8
@@ -162,7 +170,7 @@ def test_stream_entry_points_validate_before_any_launch(lib):
     assert lib.fltop_ctc_stream_state_bytes(B, Ttot, 8) < lib.fltop_ctc_stream_state_bytes(B, 2 * Ttot, 8)
     assert lib.fltop_ctc_stream_state_bytes(0, Ttot, 8) == 0
     assert lib.fltop_ctc_stream_state_bytes(B, 0, 8) == 0
-    assert lib.fltop_ctc_stream_state_bytes(B, Ttot, binding.MAX_BEAM + 1) == 0
+    assert lib.fltop_ctc_stream_state_bytes(B, Ttot, binding.MAX_BEAM_STREAMING + 1) == 0
 
     assert lib.fltop_ctc_stream_begin(None, st_need, B, Ttot, 8, None) == -1
     assert lib.fltop_ctc_stream_begin(fake, st_need - 1, B, Ttot, 8, None) == -5

@@ -344,9 +344,9 @@ def test_workload_cfg5(dev, oracle_lib, r):
 
 # --------------------------------------------------------------------------- size limits
 def test_largest_vocabulary_and_beam(dev, oracle_lib):
-    """V = FLTOP_MAX_VOCAB, beam = FLTOP_MAX_BEAM: every lane chunk of the prune stage and every
-    beam slot of the search stage is in use (and the LDS budget is at its largest)."""
-    V, beam = binding.MAX_VOCAB, binding.MAX_BEAM
+    """V = FLTOP_MAX_VOCAB with the largest beam that takes it (512): every lane chunk of the
+    prune stage and every beam slot of the 512-entry build is in use."""
+    V, beam = binding.MAX_VOCAB, 512
     lp = synth.random_emissions(4096, 2, 5, V, flat=3.0)
     ln = np.array([5, 3], dtype=np.int32)
     for r in (0.0, 0.002):
@@ -367,9 +367,11 @@ def test_largest_vocabulary_and_beam(dev, oracle_lib):
     assert (counts[:5] == V).all() and (counts[5:8] == V).all() and (counts[8:] == 0).all()
 
 
-@pytest.mark.parametrize("beam", [129, 200, 300, 512])
+@pytest.mark.parametrize("beam", [129, 200, 300, 512, 513, 1000, 1024])
 def test_beams_above_the_small_capacity(dev, oracle_lib, beam):
-    """Beams above 128 entries run the 512-entry build of the search stage."""
+    """Beams above 128 entries run the 512-entry build of the search stage, beams above 512 the
+    1024-entry build (1024 threads, part of the beam state in global memory): the paper's
+    decoder runs beam-size 1000 with a score window of 25 (Sec. 4)."""
     for seed, (B, T, V, r, window) in enumerate([(2, 80, 32, 0.0, 0.0), (3, 120, 32, 0.01, 8.0),
                                                  (2, 60, 64, 0.0, 25.0)]):
         lp = synth.random_emissions(500 + beam + seed, B, T, V, flat=1.2)
@@ -396,6 +398,38 @@ def test_beams_above_the_small_capacity(dev, oracle_lib, beam):
                 assert tuple(nt[e, :nl[e]].tolist()) == ref[e][0], f"entry {e}"
                 for g, w in ((pb[e], ref[e][1]), (pnb[e], ref[e][2])):
                     assert (g == w) or abs(g - w) <= 1e-9
+
+
+def test_largest_beam_with_its_largest_vocabulary(dev, oracle_lib):
+    """beam = FLTOP_MAX_BEAM with V = FLTOP_MAX_VOCAB_WIDE_BEAM (the LDS budget at its largest),
+    with a bigram table in global memory and with one in LDS; larger vocabularies and the
+    streaming entry points refuse such a beam."""
+    beam, V = binding.MAX_BEAM, binding.MAX_VOCAB_WIDE_BEAM
+    lp = synth.random_emissions(2048, 2, 6, V, flat=3.0)
+    ln = np.array([6, 4], dtype=np.int32)
+    lm = synth.make_bigram_lm(V, seed=9)
+    for r, table in ((0.0, None), (0.002, lm)):
+        kw = {} if table is None else dict(lm_table=table, lm_weight=0.5, insertion_bonus=1.0)
+        want = oracle_lib.decode(lp, ln, beam, r, n_threads=2, **kw)
+        got = gpu_decode(dev, lp, ln, beam, r, table, 0.5 if table is not None else 0.0,
+                         1.0 if table is not None else 0.0)
+        assert_parity(got, want[0], want[1], want[2], f"V{V} beam{beam} r{r}")
+    lm64 = synth.make_bigram_lm(64, seed=3)
+    lp2 = synth.random_emissions(2049, 2, 30, 64, flat=1.5)
+    ln2 = np.array([30, 13], dtype=np.int32)
+    want = oracle_lib.decode(lp2, ln2, beam, 0.0, lm_table=lm64, lm_weight=0.5, insertion_bonus=1.0,
+                             n_threads=2)
+    got = gpu_decode(dev, lp2, ln2, beam, 0.0, lm64, 0.5, 1.0, nbest=True)
+    assert_parity(got, want[0], want[1], want[2], "V64 beam 1024 with LM in LDS")
+    ref = oracle_lib.decode_beam(lp2[0], beam, 0.0, lm_table=lm64, lm_weight=0.5,
+                                 insertion_bonus=1.0, max_entries=beam)
+    assert [e[0] for e in got["nbest"][0]] == [e[0] for e in ref]
+    big = torch.zeros((1, 2, V + 1), device=dev)
+    with pytest.raises(binding.FltopError) as e:
+        binding.decode(big, torch.full((1,), 2, dtype=torch.int32, device=dev), beam, 0.0,
+                       workspace=torch.empty(1 << 20, dtype=torch.uint8, device=dev))
+    assert e.value.status == -3
+    assert binding.load().fltop_ctc_stream_state_bytes(2, 10, binding.MAX_BEAM_STREAMING + 1) == 0
 
 
 def test_more_utterances_than_one_grid_dimension_holds(dev, oracle_lib):
@@ -516,7 +550,7 @@ def test_two_million_candidates_per_frame(dev, oracle_lib):
     """512 beam entries x 4095 tokens: candidate numbers pass 2^20, where the reciprocal
     that splits a number into (entry, token) rounds to the next entry for the last token
     of an entry.  Frame 2 makes exactly that token the best one."""
-    V, beam = binding.MAX_VOCAB, binding.MAX_BEAM
+    V, beam = binding.MAX_VOCAB, 512
     lp = synth.random_emissions(4098, 1, 4, V, flat=1.0)
     lp[0, 2, V - 1] += 9.0  # rows need not be normalised
     ln = np.array([4], dtype=np.int32)

@@ -16,9 +16,9 @@ VOCABS = [2, 3, 7, 32, 33, 64, 65, 100, 500, 1024, 2933, 4096]
 BEAMS = [1, 2, 7, 32, 64, 65, 128, 129, 300, 512]
 
 
-def draw_case(rng, seed):
-    V = int(rng.choice(VOCABS))
-    beam = int(rng.choice(BEAMS))
+def draw_case(rng, seed, vocabs=VOCABS, beams=BEAMS):
+    V = int(rng.choice(vocabs))
+    beam = int(rng.choice(beams))
     r = float(rng.choice([0.0, 0.0, 1e-4, 1e-3, 0.01, 0.1, 0.5, 1.0]))
     top_n = int(rng.choice([0, 0, 1, 2, 4, 7, 50]))
     window = float(rng.choice([0.0, 0.0, 0.5, 3.0, 25.0]))
@@ -78,3 +78,21 @@ def test_random_configurations(oracle_lib, seed0):
         fb = out["frame_beam"].cpu().numpy()
         for b in range(len(ln)):
             np.testing.assert_array_equal(fb[b, :ln[b]], want_st["frame_beam"][b, :ln[b]], label)
+
+
+@pytest.mark.parametrize("seed0", [21, 22])
+def test_random_configurations_with_beams_beyond_512(oracle_lib, seed0):
+    """The same generator over the beam sizes of the 1024-entry build (and a few below, so
+    that the three capacities alternate), vocabularies up to its limit.  Utterances the oracle
+    reports as decided by an exact tie (quantised emissions) are held to the tie contract of
+    tests/test_gpu_ties.py, all others to the full bar."""
+    from test_gpu_ties import check_case
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    dev = torch.device("cuda:0")
+    rng = np.random.default_rng(seed0)
+    for case in range(40):
+        lp, ln, beam, r, top_n, window, lm, label = draw_case(
+            rng, seed0 * 1000 + case, vocabs=[2, 5, 32, 33, 100, 700, binding.MAX_VOCAB_WIDE_BEAM],
+            beams=[100, 512, 513, 600, 1000, 1023, binding.MAX_BEAM])
+        check_case(dev, oracle_lib, lp, ln, beam, r, top_n, window,
+                   f"seed {seed0} case {case}: {label}", lm=lm, lm_weight=0.7, insertion_bonus=0.3)

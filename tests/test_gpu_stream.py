@@ -186,7 +186,7 @@ def test_transcript_is_rewritten_only_where_it_changed(dev, oracle_lib):
 
 def test_stream_argument_errors(dev):
     assert binding.load().fltop_ctc_stream_state_bytes(0, 10, 4) == 0
-    assert binding.load().fltop_ctc_stream_state_bytes(2, 10, binding.MAX_BEAM + 1) == 0
+    assert binding.load().fltop_ctc_stream_state_bytes(2, 10, binding.MAX_BEAM_STREAMING + 1) == 0
     st = binding.Stream(1, 8, 4, 8, 4, 0.1, dev)
     with pytest.raises(ValueError):
         st.feed(torch.zeros((1, 5, 8), dtype=torch.float32, device=dev),

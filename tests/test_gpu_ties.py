@@ -35,32 +35,45 @@ def quantised(seed, B, T, V, flat):
     return (np.round(lp * 2) / 2).astype(np.float32)
 
 
-def check_case(dev, oracle_lib, lp, ln, beam, r, top_n, window, label):
+def check_case(dev, oracle_lib, lp, ln, beam, r, top_n, window, label, lm=None, lm_weight=0.0,
+               insertion_bonus=0.0):
     B, T, V = lp.shape
-    want_tok, want_sc, st = oracle_lib.decode(lp, ln, beam, r, top_n=top_n, beam_threshold=window,
-                                              n_threads=8, traces=True)
+    okw = dict(top_n=top_n, beam_threshold=window)
+    gkw = dict(okw)
+    if lm is not None:
+        okw.update(lm_table=lm, lm_weight=lm_weight, insertion_bonus=insertion_bonus)
+        gkw.update(lm_table=torch.from_numpy(lm).to(dev), lm_weight=lm_weight,
+                   insertion_bonus=insertion_bonus)
+    want_tok, want_sc, st = oracle_lib.decode(lp, ln, beam, r, n_threads=8, traces=True, **okw)
     out = binding.decode(torch.from_numpy(lp).to(dev), torch.from_numpy(ln).to(dev), beam, r,
-                         top_n=top_n, beam_threshold=window, want_traces=True, want_stats=True)
+                         want_traces=True, want_stats=True, **gkw)
     torch.cuda.synchronize()
     lens = out["lengths"].cpu().numpy()
     toks = out["tokens"].cpu().numpy()
     scores = out["scores"].cpu().numpy()
     fb = out["frame_beam"].cpu().numpy()
-    assert binding.stats_dict(out["stats"])["overflow_drops"] == 0
+    got_st = binding.stats_dict(out["stats"])
+    assert got_st["overflow_drops"] == 0
+    assert got_st["frames"] == st["frames"] and got_st["sum_survivors"] == st["sum_survivors"]
+    if min(st["margins"], default=1.0) > TIE_MARGIN:  # no tie anywhere: every count must agree
+        for key in ("sum_candidates", "peak_candidates", "sum_beam"):
+            assert got_st[key] == st[key], (label, key)
     n_tied = n_other_choice = 0
     for b in range(B):
         got = toks[b, :lens[b]].tolist()
         if st["margins"][b] > TIE_MARGIN:  # nothing was close: the full bar
             assert got == want_tok[b], f"{label}: utterance {b} tokens differ"
-            assert abs(float(scores[b]) - float(np.float32(want_sc[b]))) <= SCORE_TOL
+            if np.isfinite(want_sc[b]):
+                assert abs(float(scores[b]) - float(np.float32(want_sc[b]))) <= SCORE_TOL
+            else:
+                assert scores[b] == np.float32(want_sc[b])
             np.testing.assert_array_equal(fb[b, :ln[b]], st["frame_beam"][b, :ln[b]])
             continue
         n_tied += 1
         if ln[b] == 0:
             assert got == []
             continue
-        final = oracle_lib.decode_beam(lp[b, :ln[b]], beam, r, top_n=top_n, beam_threshold=window,
-                                       max_entries=beam)
+        final = oracle_lib.decode_beam(lp[b, :ln[b]], beam, r, max_entries=beam, **okw)
         totals = {tok: np.logaddexp(pb, pnb) for tok, pb, pnb in final}
         assert tuple(got) in totals, f"{label}: utterance {b}: GPU prefix not in the oracle's final beam"
         mine = totals[tuple(got)]

@@ -163,11 +163,9 @@ def prune_bytes(w, stats):
 
 
 def prune_written_bytes(stats):
-    """What the prune stage writes, roughly: one 64-byte header line per valid frame (count,
-    top emission, survivors 0..5) and 8 bytes per survivor beyond the sixth of a frame (the
-    latter estimated from the batch totals, exact when every frame has at least six)."""
-    extra = max(0, stats["sum_survivors"] - 6 * stats["frames"])
-    return 64 * stats["frames"] + 8 * extra
+    """What the prune stage writes: one 64-byte header line per valid frame (count, top
+    emission, survivors 0..5) and 8 bytes per survivor beyond the sixth of a frame."""
+    return 64 * stats["frames"] + 8 * stats["survivor_records"]
 
 
 def batch_time_ms(torch, fn, reps, warm=3):
@@ -562,7 +560,13 @@ def per_config(torch, binding, synth, dev, steps=20, cpu=True):
                    "full_path_frames_longest_utterance": int(full.max()),
                    "cycles_per_full_path_frame": round(search_avg * 1e-3 * CLOCK_GHZ * 1e9
                                                        / max(1, int(full.max())), 0),
-                   "workspace_bytes": int(job.ws.numel())}
+                   # the memory side of the pruning (paper Sec. 4.4): survivors beyond the six in a
+                   # frame's header take an 8-byte record each; a workspace sized for what this
+                   # input keeps against the one that is safe for any input of these shapes
+                   "survivor_records": st["survivor_records"],
+                   "workspace_bytes_for_these_survivors": binding.workspace_bytes(
+                       w.B, w.T, w.V, w.beam, max_records=st["survivor_records"]),
+                   "workspace_bytes_worst_case": int(job.ws.numel())}
             if cpu:
                 lm = job.lm_host
                 rec["cpu_oracle"] = {
@@ -582,7 +586,9 @@ def per_config(torch, binding, synth, dev, steps=20, cpu=True):
             rec["vs_unpruned"] = {
                 "gpu_speedup": round(base["ms_per_step"] / rec["ms_per_step"], 2),
                 "mean_candidates_ratio": round(base["mean_candidates"] / rec["mean_candidates"], 2),
-                "peak_candidates_ratio": round(base["peak_candidates"] / max(1, rec["peak_candidates"]), 2)}
+                "peak_candidates_ratio": round(base["peak_candidates"] / max(1, rec["peak_candidates"]), 2),
+                "workspace_bytes_ratio": round(base["workspace_bytes_for_these_survivors"]
+                                               / rec["workspace_bytes_for_these_survivors"], 2)}
             if cpu:
                 rec["vs_unpruned"]["cpu_oracle_speedup"] = round(
                     rec["cpu_oracle"]["all_cores"]["frames_per_s"]
@@ -872,7 +878,10 @@ def main():
         "stage_us": {"prune": round(prune_avg * 1e3, 2), "search": round(search_avg * 1e3, 2)},
         "mean_survivors": round(st["sum_survivors"] / max(1, st["frames"]), 3),
         "mean_candidates": round(st["sum_candidates"] / max(1, st["frames"]), 2),
-        "workspace_bytes": int(job.ws.numel()),
+        "survivor_records": st["survivor_records"],
+        "workspace_bytes_for_these_survivors": binding.workspace_bytes(
+            w.B, w.T, w.V, w.beam, max_records=st["survivor_records"]),
+        "workspace_bytes_worst_case": int(job.ws.numel()),
         "roofline": roofline,
     }
     del job

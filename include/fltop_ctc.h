@@ -58,7 +58,8 @@ extern "C" {
 #define FLTOP_ERR_BAD_BEAM       -3  /* beam < 1 or > FLTOP_MAX_BEAM; or beam > 512 together
                                         with V > FLTOP_MAX_VOCAB_WIDE_BEAM or with streaming */
 #define FLTOP_ERR_BAD_THRESHOLD  -4  /* rel_threshold outside [0, 1] or NaN                 */
-#define FLTOP_ERR_WORKSPACE      -5  /* workspace smaller than fltop_ctc_workspace_bytes()  */
+#define FLTOP_ERR_WORKSPACE      -5  /* workspace smaller than fltop_ctc_workspace_bytes_for(
+                                        ..., 0)                                             */
 #define FLTOP_ERR_VOCAB_TOO_BIG  -6  /* V > FLTOP_MAX_VOCAB                                 */
 #define FLTOP_ERR_HIP            -7  /* a HIP call or kernel launch failed                  */
 #define FLTOP_ERR_ALIGNMENT      -8  /* workspace not 256-byte aligned                      */
@@ -114,6 +115,10 @@ typedef struct fltop_stats {
                                    ranking                                                     */
     uint64_t overflow_drops;    /* entries dropped because a hash collision overfilled a beam
                                    (0 unless two different prefixes share a 64-bit hash)       */
+    uint64_t survivor_records;  /* records the survivor lists asked for: the max_records this
+                                   input needs (fltop_ctc_workspace_bytes_for)                 */
+    uint64_t record_overflows;  /* utterances not decoded because a frame's survivor records
+                                   did not fit the workspace (their out_lengths are -1)        */
 #ifdef FLTOP_PHASE_CLOCKS
     uint64_t phase_clocks[64];  /* profiling builds only (library AND caller compiled with
                                    -DFLTOP_PHASE_CLOCKS): shader-clock cycles per phase of the
@@ -122,10 +127,24 @@ typedef struct fltop_stats {
 #endif
 } fltop_stats;
 
-/* Bytes of device workspace fltop_ctc_decode / fltop_ctc_prune need for these
- * shapes (0 if the shapes are invalid).  Holds the per-frame survivor lists
- * and the prefix trie. */
+/* Bytes of device workspace that are enough for these shapes whatever the emissions and the
+ * threshold are (0 if the shapes are invalid).  Holds the per-frame survivor lists and the
+ * prefix trie. */
 size_t fltop_ctc_workspace_bytes(int32_t B, int32_t T, int32_t V, int32_t beam);
+
+/* The same for a caller who knows how little the pruning leaves (the method's memory saving,
+ * paper Sec. 4.4): a frame keeps its first six survivors in a fixed 64-byte header and every
+ * further one in an 8-byte record, and this workspace has room for `max_records` records in
+ * all.  Every entry point accepts any workspace of at least
+ * fltop_ctc_workspace_bytes_for(B, T, V, beam, 0) bytes and uses what lies beyond the fixed
+ * regions for records (never more than the shapes can need: B * T * (V - 6)).  If the
+ * survivor lists of a call ask for more, nothing is written out of bounds: the utterances
+ * that meet a frame whose records did not fit are not decoded -- out_lengths[b] = -1,
+ * out_scores[b] = NaN, stats->record_overflows counts them -- and the caller retries with
+ * a larger workspace (stats->survivor_records says how many records the call asked for).
+ * fltop_ctc_workspace_bytes(...) is this function at max_records = B * T * (V - 6). */
+size_t fltop_ctc_workspace_bytes_for(int32_t B, int32_t T, int32_t V, int32_t beam,
+                                     uint64_t max_records);
 
 /* The whole path: survivor lists for all valid frames, then the beam search,
  * then the best prefix of every utterance.
@@ -133,9 +152,11 @@ size_t fltop_ctc_workspace_bytes(int32_t B, int32_t T, int32_t V, int32_t beam);
  *                allowed; NaN is undefined.  Rows need not be normalised.
  *   lengths      dev [B] int32; values are clamped to [0,T]; frames at or
  *                beyond lengths[b] are never read.
- *   workspace    dev, 256-byte aligned, >= fltop_ctc_workspace_bytes(B,T,V,beam).
+ *   workspace    dev, 256-byte aligned, >= fltop_ctc_workspace_bytes_for(B,T,V,beam,0); with
+ *                fltop_ctc_workspace_bytes(B,T,V,beam) bytes no input can overflow it.
  *   out_tokens   dev [B,T] int32; row b holds out_lengths[b] tokens (rest untouched).
- *   out_lengths  dev [B] int32.
+ *   out_lengths  dev [B] int32 (-1: not decoded, the workspace was too small for the
+ *                utterance's survivor lists).
  *   out_scores   dev [B] fp32: LSE(p_b,p_nb) of the returned prefix, rounded
  *                from fp64.  A zero-length utterance returns the empty prefix
  *                with score 0; an utterance whose every route has zero mass
@@ -153,11 +174,14 @@ int fltop_ctc_decode(const float* logprobs, const int32_t* lengths,
  * survivor lists and the prefix trie go into an array of FLTOP_STATIC_SCRATCH_BYTES that is
  * part of the library's device image (every GPU the library runs on holds its own copy until
  * the process ends); the call allocates and frees nothing.  Inputs, outputs, argument rules
- * and results are those of fltop_ctc_decode.  Shapes for which fltop_ctc_workspace_bytes()
- * exceeds FLTOP_STATIC_SCRATCH_BYTES are refused with FLTOP_ERR_STATIC_SCRATCH before anything
- * is enqueued.  All calls on one GPU share the one array, whatever their stream: calls that
- * overlap in time on one GPU race, so order them (one stream, or events).  Nothing in the
- * array has to be cleared between calls: each call writes what it later reads. */
+ * and results are those of fltop_ctc_decode with a workspace of that size: shapes whose fixed
+ * regions alone (fltop_ctc_workspace_bytes_for(B, T, V, beam, 0)) exceed it are refused with
+ * FLTOP_ERR_STATIC_SCRATCH before anything is enqueued; survivor records take the rest of the
+ * array, and a call whose survivor lists ask for more reports the utterances concerned as
+ * fltop_ctc_workspace_bytes_for describes.  All calls on one GPU share the one array,
+ * whatever their stream: calls that overlap in time on one GPU race, so order them (one
+ * stream, or events).  Nothing in the array has to be cleared between calls: each call writes
+ * what it later reads. */
 #define FLTOP_STATIC_SCRATCH_BYTES (64u << 20)
 int fltop_ctc_decode_static(const float* logprobs, const int32_t* lengths,
                             int32_t B, int32_t T, int32_t V, const fltop_params* params,

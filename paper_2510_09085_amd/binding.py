@@ -22,7 +22,8 @@ MAX_VOCAB = 4096
 
 STATIC_SCRATCH_BYTES = 64 << 20
 
-EXPORTS = ("fltop_ctc_workspace_bytes", "fltop_ctc_decode", "fltop_ctc_decode_static",
+EXPORTS = ("fltop_ctc_workspace_bytes", "fltop_ctc_workspace_bytes_for", "fltop_ctc_decode",
+           "fltop_ctc_decode_static",
            "fltop_ctc_prune", "fltop_ctc_search",
            "fltop_ctc_unpack_survivors", "fltop_ctc_token_ranks", "fltop_ctc_stream_state_bytes",
            "fltop_ctc_stream_begin", "fltop_ctc_stream_decode", "fltop_ctc_log_add",
@@ -50,8 +51,9 @@ class FltopParams(ctypes.Structure):
 
 
 STATS_FIELDS = ("frames", "sum_survivors", "sum_candidates", "peak_candidates", "sum_beam",
-                "select_passes", "exact_rankings", "overflow_drops")
-# words to allocate for a fltop_stats block: the eight counters, and room for the 4 x 16 phase
+                "select_passes", "exact_rankings", "overflow_drops", "survivor_records",
+                "record_overflows")
+# words to allocate for a fltop_stats block: the ten counters, and room for the 4 x 16 phase
 # clocks that a profiling build of the library (-DFLTOP_PHASE_CLOCKS) appends
 STATS_WORDS = len(STATS_FIELDS) + 64
 
@@ -76,6 +78,8 @@ def load():
     vp, i32, f32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_float, ctypes.c_size_t
     lib.fltop_ctc_workspace_bytes.restype = sz
     lib.fltop_ctc_workspace_bytes.argtypes = [i32, i32, i32, i32]
+    lib.fltop_ctc_workspace_bytes_for.restype = sz
+    lib.fltop_ctc_workspace_bytes_for.argtypes = [i32, i32, i32, i32, ctypes.c_uint64]
     lib.fltop_ctc_decode.restype = ctypes.c_int
     lib.fltop_ctc_decode.argtypes = [vp, vp, i32, i32, i32, ctypes.POINTER(FltopParams), vp, sz,
                                      vp, vp, vp, vp, vp]
@@ -110,8 +114,12 @@ def status_string(status: int) -> str:
     return load().fltop_status_string(int(status)).decode()
 
 
-def workspace_bytes(B: int, T: int, V: int, beam: int) -> int:
-    return int(load().fltop_ctc_workspace_bytes(B, T, V, beam))
+def workspace_bytes(B: int, T: int, V: int, beam: int, max_records: Optional[int] = None) -> int:
+    """Bytes that hold any input of these shapes, or (max_records given) the fixed regions plus
+    room for that many survivor records beyond the six per frame that sit in the headers."""
+    if max_records is None:
+        return int(load().fltop_ctc_workspace_bytes(B, T, V, beam))
+    return int(load().fltop_ctc_workspace_bytes_for(B, T, V, beam, int(max_records)))
 
 
 def _ptr(t: Optional[torch.Tensor]):
@@ -135,8 +143,9 @@ def _check_inputs(logprobs: torch.Tensor, lengths: torch.Tensor):
         raise ValueError("lengths must have B entries")
 
 
-def alloc_workspace(B: int, T: int, V: int, beam: int, device) -> torch.Tensor:
-    n = workspace_bytes(B, T, V, beam)
+def alloc_workspace(B: int, T: int, V: int, beam: int, device,
+                    max_records: Optional[int] = None) -> torch.Tensor:
+    n = workspace_bytes(B, T, V, beam, max_records)
     if n == 0:
         raise FltopError(-2, "fltop_ctc_workspace_bytes")
     return torch.empty(n, dtype=torch.uint8, device=device)

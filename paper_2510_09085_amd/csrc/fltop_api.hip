@@ -34,6 +34,18 @@ int check_workspace(const void* ws, size_t bytes, size_t need) {
     return FLTOP_OK;
 }
 
+// The caller's workspace laid out for these shapes: the fixed regions, and behind them as many
+// survivor records as the remaining bytes hold.
+int lay_out(void* workspace, size_t bytes, int32_t B, int32_t T, int32_t V, int32_t beam,
+            fltop::Workspace* ws) {
+    if (!workspace) return FLTOP_ERR_NULL_POINTER;
+    if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return FLTOP_ERR_ALIGNMENT;
+    const int64_t records = fltop::records_that_fit(bytes, B, T, V, beam);
+    if (records < 0) return FLTOP_ERR_WORKSPACE;
+    *ws = fltop::carve_workspace(workspace, B, T, V, beam, (uint64_t)records);
+    return FLTOP_OK;
+}
+
 // ln(R) rounded to fp32 once; R = 0 keeps everything.
 float ln_threshold(float r) {
     if (r <= 0.0f) return -INFINITY;
@@ -42,9 +54,20 @@ float ln_threshold(float r) {
 
 }  // namespace
 
-extern "C" size_t fltop_ctc_workspace_bytes(int32_t B, int32_t T, int32_t V, int32_t beam) {
+extern "C" size_t fltop_ctc_workspace_bytes_for(int32_t B, int32_t T, int32_t V, int32_t beam,
+                                                uint64_t max_records) {
     if (check_shapes(B, T, V, beam) != FLTOP_OK) return 0;
-    return fltop::carve_workspace(nullptr, B, T, V, beam).bytes;
+    // the budget asked for (never more than the shapes can need), plus the slack that makes
+    // all of it usable, rounded up to whole slices
+    const uint64_t most = fltop::worst_case_records(B, T, V);
+    uint64_t n = (max_records < most ? max_records : most);
+    if (n > 0) n += fltop::record_slack(V);
+    n = (n + fltop::kRecArenas - 1) / fltop::kRecArenas * fltop::kRecArenas;
+    return fltop::carve_workspace(nullptr, B, T, V, beam, n).bytes;
+}
+
+extern "C" size_t fltop_ctc_workspace_bytes(int32_t B, int32_t T, int32_t V, int32_t beam) {
+    return fltop_ctc_workspace_bytes_for(B, T, V, beam, ~0ull);
 }
 
 extern "C" int fltop_ctc_prune(const float* logprobs, const int32_t* lengths, int32_t B, int32_t T,
@@ -57,9 +80,9 @@ extern "C" int fltop_ctc_prune(const float* logprobs, const int32_t* lengths, in
     if (rc != FLTOP_OK) return rc;
     rc = check_options(top_n, 0.0);
     if (rc != FLTOP_OK) return rc;
-    rc = check_workspace(workspace, workspace_bytes, fltop_ctc_workspace_bytes(B, T, V, beam));
+    fltop::Workspace ws;
+    rc = lay_out(workspace, workspace_bytes, B, T, V, beam, &ws);
     if (rc != FLTOP_OK) return rc;
-    const fltop::Workspace ws = fltop::carve_workspace(workspace, B, T, V, beam);
     hipError_t e = fltop::launch_prune(logprobs, lengths, B, T, V, ln_threshold(rel_threshold),
                                        top_n, ws, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? FLTOP_OK : FLTOP_ERR_HIP;
@@ -73,10 +96,9 @@ extern "C" int fltop_ctc_unpack_survivors(const void* workspace, size_t workspac
     if (!lengths || !counts || !tokens || !values) return FLTOP_ERR_NULL_POINTER;
     int rc = check_shapes(B, T, V, beam);
     if (rc != FLTOP_OK) return rc;
-    rc = check_workspace(workspace, workspace_bytes, fltop_ctc_workspace_bytes(B, T, V, beam));
+    fltop::Workspace ws;
+    rc = lay_out(const_cast<void*>(workspace), workspace_bytes, B, T, V, beam, &ws);
     if (rc != FLTOP_OK) return rc;
-    const fltop::Workspace ws =
-        fltop::carve_workspace(const_cast<void*>(workspace), B, T, V, beam);
     hipError_t e = fltop::launch_unpack(ws, lengths, B, T, V, counts, tokens, values, frame_max,
                                         static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? FLTOP_OK : FLTOP_ERR_HIP;
@@ -121,10 +143,9 @@ extern "C" int fltop_ctc_search(const int32_t* lengths, int32_t B, int32_t T, in
     if (rc != FLTOP_OK) return rc;
     rc = check_nbest(params);
     if (rc != FLTOP_OK) return rc;
-    rc = check_workspace(workspace, workspace_bytes,
-                         fltop_ctc_workspace_bytes(B, T, V, params->beam));
+    fltop::Workspace ws;
+    rc = lay_out(workspace, workspace_bytes, B, T, V, params->beam, &ws);
     if (rc != FLTOP_OK) return rc;
-    const fltop::Workspace ws = fltop::carve_workspace(workspace, B, T, V, params->beam);
     return enqueue_search(lengths, B, T, V, params, ws, nullptr, out_tokens, out_lengths,
                           out_scores, stats, static_cast<hipStream_t>(hip_stream));
 }
@@ -143,12 +164,11 @@ extern "C" int fltop_ctc_decode(const float* logprobs, const int32_t* lengths, i
     if (rc != FLTOP_OK) return rc;
     rc = check_nbest(params);
     if (rc != FLTOP_OK) return rc;
-    rc = check_workspace(workspace, workspace_bytes,
-                         fltop_ctc_workspace_bytes(B, T, V, params->beam));
+    fltop::Workspace ws;
+    rc = lay_out(workspace, workspace_bytes, B, T, V, params->beam, &ws);
     if (rc != FLTOP_OK) return rc;
 
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    const fltop::Workspace ws = fltop::carve_workspace(workspace, B, T, V, params->beam);
     hipError_t e = fltop::launch_prune(logprobs, lengths, B, T, V,
                                        ln_threshold(params->rel_threshold), params->top_n, ws,
                                        stream);
@@ -199,7 +219,8 @@ extern "C" int fltop_ctc_decode_static(const float* logprobs, const int32_t* len
                                        int32_t* out_tokens, int32_t* out_lengths,
                                        float* out_scores, fltop_stats* stats, void* hip_stream) {
     if (!params) return FLTOP_ERR_NULL_POINTER;
-    const size_t need = fltop_ctc_workspace_bytes(B, T, V, params->beam);
+    // what the shapes need whatever the survivor lists hold; records take the rest of the array
+    const size_t need = fltop_ctc_workspace_bytes_for(B, T, V, params->beam, 0);
     if (need > (size_t)FLTOP_STATIC_SCRATCH_BYTES) return FLTOP_ERR_STATIC_SCRATCH;
     hipError_t e = hipSuccess;
     void* at = fetch_scratch(&e);
@@ -246,15 +267,14 @@ extern "C" int fltop_ctc_stream_decode(const float* logprobs, const int32_t* len
     if (rc != FLTOP_OK) return rc;
     rc = check_nbest(params);
     if (rc != FLTOP_OK) return rc;
-    rc = check_workspace(workspace, workspace_bytes,
-                         fltop_ctc_workspace_bytes(B, T_chunk, V, params->beam));
+    fltop::Workspace ws;
+    rc = lay_out(workspace, workspace_bytes, B, T_chunk, V, params->beam, &ws);
     if (rc != FLTOP_OK) return rc;
     rc = check_workspace(state, state_bytes,
                          fltop_ctc_stream_state_bytes(B, T_total, params->beam));
     if (rc != FLTOP_OK) return rc;
 
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    const fltop::Workspace ws = fltop::carve_workspace(workspace, B, T_chunk, V, params->beam);
     const fltop::StreamSpace sp = fltop::carve_stream(state, B, T_total, params->beam);
     hipError_t e = fltop::launch_prune(logprobs, lengths, B, T_chunk, V,
                                        ln_threshold(params->rel_threshold), params->top_n, ws,
@@ -300,7 +320,7 @@ extern "C" const char* fltop_status_string(int status) {
         case FLTOP_ERR_ALIGNMENT: return "workspace not 256-byte aligned";
         case FLTOP_ERR_BAD_OPTION: return "top_n negative or beam_threshold NaN";
         case FLTOP_ERR_STATIC_SCRATCH:
-            return "shapes need more workspace than FLTOP_STATIC_SCRATCH_BYTES";
+            return "shapes need more workspace than FLTOP_STATIC_SCRATCH_BYTES";  // fixed regions
         default: return "unknown status";
     }
 }

@@ -402,7 +402,7 @@ __host__ __device__ inline size_t lm_lds_offset(int V, bool with_s_lp) {
 // What a frame header holds besides survivors 2..5 (one 32-byte LDS read).
 struct HdrHead {
     int32_t count;
-    int32_t has_blank;
+    uint32_t rec_base;
     float top;
     uint32_t div_magic;
     Survivor s0, s1;
@@ -816,6 +816,7 @@ void beam_kernel(BeamArgs a) {
     __shared__ uint64_t sh_selD, sh_selH, sh_kbest;
     __shared__ uint64_t sh_minD;  // smallest distance (= best score) among a frame's candidates
     __shared__ int32_t sh_nnew, sh_blcount, sh_best;
+    __shared__ unsigned long long sh_stat[8];
     __shared__ __align__(16) int32_t newslot[kMaxBeam];  // old beam index -> new beam index of an entry that stays
     extern __shared__ __align__(16) unsigned char dyn_lds[];
 
@@ -890,6 +891,7 @@ void beam_kernel(BeamArgs a) {
         sh_blcount = 0;
         sh_minD = kAllOnes;
     }
+    if (tid < 8) sh_stat[tid] = 0ull;
     if (carried) {  // the beam as the previous chunk left it
         __syncthreads();  // the link arrays were just preset by other threads
         const uint32_t* src = reinterpret_cast<const uint32_t*>(&carried->slab);
@@ -939,6 +941,7 @@ void beam_kernel(BeamArgs a) {
     int n_live = 1;
     bool collapsed = false;  // blank-only frames since the beam was last written
     double kmax_v = 0.0, kmin_v = 0.0;  // bounds of the best / worst score
+    bool failed = false;     // a frame's survivor records did not fit the workspace
     int prev_out_len = 0;       // streaming: length of the transcript the last call wrote ...
     uint64_t prev_tokens_at = 0, prev_frames_at = 0;  // ... and the rows it wrote it to
     if (carried) {
@@ -951,9 +954,24 @@ void beam_kernel(BeamArgs a) {
         kmin_v = carried->kmin;
     }
 
-    // statistics kept by thread 0
-    uint64_t st_surv = 0, st_cand = 0, st_peak = 0, st_beam = 0, st_pass = 0, st_exact = 0,
-             st_drop = 0;
+    // Statistics of this utterance live in LDS, not in 64-bit registers that every thread would
+    // carry through the whole kernel.  What the frames of one chunk add up to is wave-uniform
+    // and collects in 32-bit counters (scalar registers); once per chunk the last thread of the
+    // workgroup (its wavefront has the least to do) moves them into LDS.
+    enum : int { kStSurv, kStCand, kStPeak, kStBeam, kStPass, kStExact, kStDrop, kStRecords };
+    const bool stat_thread = tid == kThreads - 1;
+    uint32_t pd_cand = 0, pd_peak = 0, pd_beam = 0, pd_pass = 0, pd_exact = 0, pd_drop = 0;
+    auto flush_stats = [&]() {
+        if (stat_thread) {
+            atomicAdd(&sh_stat[kStCand], (unsigned long long)pd_cand);
+            atomicMax(&sh_stat[kStPeak], (unsigned long long)pd_peak);
+            atomicAdd(&sh_stat[kStBeam], (unsigned long long)pd_beam);
+            atomicAdd(&sh_stat[kStPass], (unsigned long long)pd_pass);
+            if (pd_exact) atomicAdd(&sh_stat[kStExact], (unsigned long long)pd_exact);
+            if (pd_drop) atomicAdd(&sh_stat[kStDrop], (unsigned long long)pd_drop);
+        }
+        pd_cand = pd_peak = pd_beam = pd_pass = pd_exact = pd_drop = 0;
+    };
 #ifdef FLTOP_PHASE_CLOCKS
     constexpr int kWavesPerGroup = kThreads / kWave >= 4 ? kThreads / kWave / 4 : 1;
     const int ph_grp = (tid / kWave) / kWavesPerGroup;
@@ -985,11 +1003,20 @@ void beam_kernel(BeamArgs a) {
         lp_bits = __float_as_int(hh.s0.lp);
         const int chunk_survivors = __builtin_amdgcn_readlane(
             wave_inclusive_scan(inside ? hh.count : 0), kWave - 1);
-        if (tid == 0) st_surv += (uint64_t)chunk_survivors;
+        // records the chunk's frames take beyond the survivors in their headers
+        const int chunk_records = __builtin_amdgcn_readlane(
+            wave_inclusive_scan(inside ? max(0, hh.count - kRegK) : 0), kWave - 1);
+        flush_stats();  // of the previous chunk (at most 32 frames: the counters cannot wrap)
+        if (stat_thread) {
+            atomicAdd(&sh_stat[kStSurv], (unsigned long long)chunk_survivors);
+            if (chunk_records) atomicAdd(&sh_stat[kStRecords], (unsigned long long)chunk_records);
+        }
+        // after a frame whose records did not fit the workspace the utterance is not decoded
+        // any further, but its survivors are still counted: the caller learns what to ask for
+        if (failed) continue;
     }
 
     for (int t = c * kChunk; t < t_end; ++t) {
-        const int64_t g = g_base + t;
         const int l = t & (kChunk - 1);
         if (n_live == 0) {  // the beam died: nothing left to decode
             if (a.frame_beam && tid < t_end - t) a.frame_beam[trace_base + t + tid] = 0;
@@ -1011,11 +1038,9 @@ void beam_kernel(BeamArgs a) {
             if (tid < n_live) cur_run->ptot[tid] = own;
             collapsed = true;
             lds_barrier();  // the new totals are read by other threads in the next full frame
-            if (tid == 0) {
-                st_cand += (uint64_t)n_live * (uint64_t)run;
-                if ((uint64_t)n_live > st_peak) st_peak = (uint64_t)n_live;
-                st_beam += (uint64_t)n_live * (uint64_t)run;
-            }
+            pd_cand += (uint32_t)(n_live * run);
+            pd_peak = max(pd_peak, (uint32_t)n_live);
+            pd_beam += (uint32_t)(n_live * run);
             if (a.frame_beam && tid < run) a.frame_beam[trace_base + t + tid] = n_live;
             t += run - 1;
             PHASE_MARK(7);
@@ -1056,8 +1081,12 @@ void beam_kernel(BeamArgs a) {
         }
         if (tid >= kThreads / 2 && tid - kThreads / 2 < kMaxBeam / 4)
             reinterpret_cast<int4*>(newslot)[tid - kThreads / 2] = make_int4(-1, -1, -1, -1);
+        if (big && hd.rec_base == kNoRecords) {  // uniform: the record array was too small
+            failed = true;
+            break;
+        }
         if (big) {
-            const Survivor* recs = rec_all + g * (int64_t)V;
+            const Survivor* recs = rec_all + ((int64_t)hd.rec_base - kRegK);
             const FrameHdr* full = &ring[t % kChunk];
             for (int k = tid; k < K; k += kThreads) {
                 const Survivor s = (k < kRegK) ? full->first[k] : recs[k];
@@ -1069,7 +1098,7 @@ void beam_kernel(BeamArgs a) {
         if (big) lds_barrier();
 
         PHASE_MARK(0);
-        fc.nb0 = hd.has_blank;  // survivors ascend by token: the blank, if kept, is the first
+        fc.nb0 = hd.first[0].tok == 0 ? 1 : 0;  // survivors ascend by token: the blank, if kept, is the first
         fc.Knb = K - fc.nb0;
         fc.div_magic = hd.div_magic;
         const double lp_blank = fc.nb0 ? (double)hd.first[0].lp : -INFINITY;
@@ -1247,10 +1276,8 @@ void beam_kernel(BeamArgs a) {
                 const int incl = wave_inclusive_scan(cs);
                 const int total = __builtin_amdgcn_readlane(incl, kWave - 1);
                 if (iter == 0) {
-                    if (tid == 0) {
-                        st_cand += (uint64_t)total;
-                        if ((uint64_t)total > st_peak) st_peak = (uint64_t)total;
-                    }
+                    pd_cand += (uint32_t)total;
+                    pd_peak = max(pd_peak, (uint32_t)total);
                     // first occupied bin -> bound of the best candidate (window starts at 0)
                     const uint64_t occ = __ballot(cs > 0);
                     if (occ != 0) {
@@ -1264,7 +1291,7 @@ void beam_kernel(BeamArgs a) {
                         kbest_key = dmin > Rk ? 0 : Rk - dmin;
                     }
                 }
-                if (tid == 0) st_pass++;
+                ++pd_pass;
                 if (total <= need) {  // everything left in the window is kept
                     selD = (w.mode == 0) ? kAllOnes : w.Dfix;
                     selH = kAllOnes;
@@ -1298,7 +1325,7 @@ void beam_kernel(BeamArgs a) {
                 }
                 if (n_b <= kExactCap) {
                     // ---- exact ranking of the boundary bucket by (distance, hash)
-                    if (tid == 0) st_exact++;
+                    ++pd_exact;
                     if (D_stay != kAllOnes)
                         boundary_add(fc, w, bstar, D_stay, tid, -1, &sh_blcount, bl_D, bl_h);
                     if (cD0 != kAllOnes)
@@ -1435,12 +1462,12 @@ void beam_kernel(BeamArgs a) {
         PHASE_MARK(5);
 
         // ---- adopt the new beam; rebuild parent / children links ---------------------
-        int n_new = sh_nnew;
+        int n_new = __builtin_amdgcn_readfirstlane(sh_nnew);  // the same in every lane
         if (n_new > beam) {
-            if (tid == 0) st_drop += (uint64_t)(n_new - beam);
+            pd_drop += (uint32_t)(n_new - beam);
             n_new = beam;
         }
-        if (tid == 0) st_beam += (uint64_t)n_new;
+        pd_beam += (uint32_t)n_new;
         if (tid < n_new) {
             int p = -1;
             const int32_t code = lkn->par[tid];
@@ -1512,6 +1539,8 @@ void beam_kernel(BeamArgs a) {
 #undef FLTOP_LOAD_CHUNK
 #undef FLTOP_RING_HEAD
 
+    flush_stats();
+    if (failed) n_live = 0;  // nothing to report, and a stream that carries on finds no beam
     // every trie store must have landed before the back-walk reads the nodes
     __threadfence_block();
     __syncthreads();
@@ -1540,7 +1569,10 @@ void beam_kernel(BeamArgs a) {
 
     const int best = sh_best;
     if (tid == 0) {
-        if (best < 0) {
+        if (failed) {  // said loudly: no transcript, not an empty one
+            a.out_lengths[b] = -1;
+            a.out_scores[b] = __int_as_float(0x7fc00000);  // NaN
+        } else if (best < 0) {
             a.out_lengths[b] = 0;
             a.out_scores[b] = -INFINITY;
         } else {
@@ -1549,13 +1581,15 @@ void beam_kernel(BeamArgs a) {
         }
         if (a.stats) {
             atomicAdd((unsigned long long*)&a.stats->frames, (unsigned long long)len);
-            atomicAdd((unsigned long long*)&a.stats->sum_survivors, (unsigned long long)st_surv);
-            atomicAdd((unsigned long long*)&a.stats->sum_candidates, (unsigned long long)st_cand);
-            atomicMax((unsigned long long*)&a.stats->peak_candidates, (unsigned long long)st_peak);
-            atomicAdd((unsigned long long*)&a.stats->sum_beam, (unsigned long long)st_beam);
-            atomicAdd((unsigned long long*)&a.stats->select_passes, (unsigned long long)st_pass);
-            atomicAdd((unsigned long long*)&a.stats->exact_rankings, (unsigned long long)st_exact);
-            atomicAdd((unsigned long long*)&a.stats->overflow_drops, (unsigned long long)st_drop);
+            atomicAdd((unsigned long long*)&a.stats->sum_survivors, sh_stat[kStSurv]);
+            atomicAdd((unsigned long long*)&a.stats->sum_candidates, sh_stat[kStCand]);
+            atomicMax((unsigned long long*)&a.stats->peak_candidates, sh_stat[kStPeak]);
+            atomicAdd((unsigned long long*)&a.stats->sum_beam, sh_stat[kStBeam]);
+            atomicAdd((unsigned long long*)&a.stats->select_passes, sh_stat[kStPass]);
+            atomicAdd((unsigned long long*)&a.stats->exact_rankings, sh_stat[kStExact]);
+            atomicAdd((unsigned long long*)&a.stats->overflow_drops, sh_stat[kStDrop]);
+            if (failed) atomicAdd((unsigned long long*)&a.stats->record_overflows, 1ull);
+            atomicAdd((unsigned long long*)&a.stats->survivor_records, sh_stat[kStRecords]);
         }
     }
 #ifdef FLTOP_PHASE_CLOCKS

@@ -13,7 +13,10 @@
 //
 // Output per frame: a 64-byte header (count, top emission, survivors 0..5 in
 // ascending token order) and, for frames with more than six survivors, survivors
-// 6.. as (token, log-prob) records at a fixed place (slot = rank).
+// 6.. as (token, log-prob) records in a stretch of the record array that the frame
+// takes from one counter (one atomic per wavefront round that needs any), so the array
+// holds what the threshold lets through and no more; a frame that finds it full is
+// marked, and the search stage reports the utterance instead of decoding it.
 //
 // Mapping: a frame is owned by LPF lanes of one wavefront (LPF = 1..64, a power
 // of two >= V/4), each lane holding 4*ITERS values in registers, so a wavefront
@@ -135,11 +138,15 @@ __device__ __forceinline__ void load_frame(FrameRegs<LPF, ITERS, VEC4>& r,
     }
 }
 
-template <int LPF, int ITERS, bool VEC4>
+// DENSE: the record array holds the worst case (every token of every frame), so frame g simply
+// owns the stretch [g * (V - 6), (g + 1) * (V - 6)) and nothing has to be counted; otherwise the
+// array is smaller and stretches are handed out as frames ask for them.
+template <int LPF, int ITERS, bool VEC4, bool DENSE>
 __global__ __launch_bounds__(kThreads) void prune_kernel(
     const float* __restrict__ logprobs, const int32_t* __restrict__ lengths, int32_t B, int32_t T,
     int32_t V, float ln_r, int32_t top_n, FrameHdr* __restrict__ hdr,
-    Survivor* __restrict__ rec) {
+    Survivor* __restrict__ rec, unsigned long long* __restrict__ rec_used,
+    uint32_t rec_capacity) {
     constexpr int FPR = kWave / LPF;  // frames per wave round
     static_assert(LPF == kWave || ITERS == 1, "several chunks per lane only for whole-wave frames");
     static_assert(ITERS <= 8 || ITERS == 16, "flag word holds 4*ITERS <= 64 bits");
@@ -179,7 +186,6 @@ __global__ __launch_bounds__(kThreads) void prune_kernel(
         for (int u = 0; u < U; ++u) {
         const int rd = base + u;
         if (rd >= n_rounds) break;
-        const int64_t g = g_base + rd * FPR + gw;
         const FrameRegs<LPF, ITERS, VEC4>& fr = cur[u];
         // ---- top emission and threshold ------------------------------------------------
         float m = -INFINITY;
@@ -196,7 +202,6 @@ __global__ __launch_bounds__(kThreads) void prune_kernel(
         // round's frames are assembled in LDS (wave-local, no barrier) and leave as
         // whole 64-byte lines, 16 bytes per lane: a partly written line would cost the
         // memory system a read-modify-write.
-        Survivor* list = rec + g * V;
         FrameHdr* img = &stage[threadIdx.x / kWave][gw];
         unsigned keep[ITERS];  // bit e of keep[it]: value x[it][e] survives
         int kept_here = 0;
@@ -262,8 +267,43 @@ __global__ __launch_bounds__(kThreads) void prune_kernel(
                 }
             }
         }
+        // ---- a place in the record array for the survivors beyond the header's six ---------
+        uint32_t rec_base = kNoRecords;
+        if (DENSE) {
+            rec_base = (uint32_t)((g_base + rd * FPR + gw) * (int64_t)max(0, V - kInlineSurvivors));
+        } else {
+        int kept_now = 0;
+#pragma unroll
+        for (int it = 0; it < ITERS; ++it) kept_now += __popc(keep[it]);
+        const int need = max(0, group_sum<LPF>(kept_now) - kInlineSurvivors);  // same in the group
+        if (__any(need > 0)) {  // wave-uniform: one request for the round's frames together
+            const int incl = group_inclusive_scan<kWave>(lg == 0 ? need : 0, lane);
+            const int wave_total = __builtin_amdgcn_readlane(incl, kWave - 1);
+            // the array is handed out in kRecArenas slices with a counter each; a request that
+            // does not fit the wavefront's own slice goes on to the next ones
+            const uint32_t per_arena = rec_capacity / kRecArenas;
+            for (int attempt = 0; attempt < kRecArenas; ++attempt) {
+                const int arena = (wave_id + (int)b + attempt) & (kRecArenas - 1);
+                unsigned long long base = 0;
+                if (lane == 0)
+                    base = atomicAdd(rec_used + arena, (unsigned long long)wave_total);
+                base = ((unsigned long long)(uint32_t)__builtin_amdgcn_readfirstlane(
+                            (int)(base >> 32)) << 32) |
+                       (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)base);
+                if (base + (unsigned long long)wave_total <= (unsigned long long)per_arena) {
+                    // every lane of a group sees the needs of the groups up to its own
+                    if (need > 0)
+                        rec_base = (uint32_t)arena * per_arena + (uint32_t)base +
+                                   (uint32_t)(incl - need);
+                    break;
+                }
+            }
+        }
+        }  // !DENSE
+        Survivor* list = rec + ((int64_t)rec_base - kInlineSurvivors);  // used only if it fits
+        const bool fits = rec_base != kNoRecords;
         // whether the blank (token 0, held by the group's first lane) survived: the search
-        // stage wants it, and the number of other survivors, ready-made
+        // stage wants the number of other survivors ready-made
         const int has_blank = group_sum<LPF>(lg == 0 ? (int)(keep[0] & 1u) : 0);
         // unused places of the header's inline list read as (token -1, log-prob -inf)
         for (int p = lg; p < 3; p += LPF)
@@ -285,7 +325,7 @@ __global__ __launch_bounds__(kThreads) void prune_kernel(
                 s.lp = e == 0 ? fr.x[it][0] : e == 1 ? fr.x[it][1] : e == 2 ? fr.x[it][2] : fr.x[it][3];
                 if (rank < kInlineSurvivors)
                     img->first[rank] = s;
-                else
+                else if (fits)
                     list[rank] = s;
                 ++rank;
             }
@@ -299,10 +339,10 @@ __global__ __launch_bounds__(kThreads) void prune_kernel(
             const uint32_t others = (uint32_t)(total - has_blank);
             int4 h;
             h.x = total;
-            h.y = has_blank;
+            h.y = (int)rec_base;
             h.z = __float_as_int(m);
             h.w = others > 1u ? (int)(0xFFFFFFFFu / others + 1u) : 0;
-            *reinterpret_cast<int4*>(img) = h;  // count, has_blank, top, div_magic
+            *reinterpret_cast<int4*>(img) = h;  // count, rec_base, top, div_magic
         }
         // LDS operations of one wavefront execute in order, so the images are complete
         // for the reads below.  Frames beyond the length get no header: never read, and
@@ -344,7 +384,7 @@ __global__ __launch_bounds__(kThreads) void unpack_kernel(
     }
     struct Head {
         int32_t count;
-        int32_t has_blank;
+        uint32_t rec_base;
         float top;
         int32_t pad;
     };
@@ -353,8 +393,10 @@ __global__ __launch_bounds__(kThreads) void unpack_kernel(
         counts[g] = h.count;
         if (frame_max) frame_max[g] = h.top;
     }
-    const Survivor* src = rec + g * V;
-    for (int k = lane; k < h.count; k += kWave) {
+    // survivors beyond the sixth sit in the frame's stretch of the record array (if they fitted)
+    const Survivor* src = rec + ((int64_t)h.rec_base - kInlineSurvivors);
+    const int have = h.rec_base == kNoRecords ? min(h.count, kInlineSurvivors) : h.count;
+    for (int k = lane; k < have; k += kWave) {
         const Survivor s = (k < kInlineSurvivors) ? hdr[g].first[k] : src[k];
         tokens[g * V + k] = s.tok;
         values[g * V + k] = s.lp;
@@ -381,6 +423,10 @@ __global__ __launch_bounds__(kThreads) void lm_bound_kernel(const float* __restr
     }
 }
 
+__global__ void clear_record_counters_kernel(unsigned long long* rec_used) {
+    rec_used[threadIdx.x] = 0ull;
+}
+
 template <int LPF, int ITERS>
 hipError_t launch_prune_t(const float* logprobs, const int32_t* lengths, int32_t B, int32_t T,
                           int32_t V, float ln_r, int32_t top_n, const Workspace& ws,
@@ -400,12 +446,25 @@ hipError_t launch_prune_t(const float* logprobs, const int32_t* lengths, int32_t
     if (bx < 1) bx = 1;
     const dim3 grid((unsigned)bx, (unsigned)(B < 65535 ? B : 65535));
     const bool vec4 = (V % 4 == 0) && ((reinterpret_cast<uintptr_t>(logprobs) & 15u) == 0);
-    if (vec4)
-        hipLaunchKernelGGL((prune_kernel<LPF, ITERS, true>), grid, dim3(kThreads), 0, stream,
-                           logprobs, lengths, B, T, V, ln_r, top_n, ws.hdr, ws.rec);
-    else
-        hipLaunchKernelGGL((prune_kernel<LPF, ITERS, false>), grid, dim3(kThreads), 0, stream,
-                           logprobs, lengths, B, T, V, ln_r, top_n, ws.hdr, ws.rec);
+    unsigned long long* const used = ws.rec_used;
+    // With room for the worst case every frame has its fixed stretch of the record array: no
+    // counters, no atomics.  A smaller array is handed out on demand (costs the prune stage a
+    // few microseconds: a global atomic with a result sits on every wavefront's path).
+    const bool dense = worst_case_records(B, T, V) <= (uint64_t)ws.rec_capacity;
+#define FLTOP_LAUNCH_PRUNE(VEC4_, DENSE_)                                                        \
+    hipLaunchKernelGGL((prune_kernel<LPF, ITERS, VEC4_, DENSE_>), grid, dim3(kThreads), 0, stream, \
+                       logprobs, lengths, B, T, V, ln_r, top_n, ws.hdr, ws.rec, used,            \
+                       ws.rec_capacity)
+    if (dense) {
+        if (vec4) FLTOP_LAUNCH_PRUNE(true, true);
+        else FLTOP_LAUNCH_PRUNE(false, true);
+    } else {
+        // a kernel, not a memset: a call may be captured into a HIP graph
+        hipLaunchKernelGGL(clear_record_counters_kernel, dim3(1), dim3(kRecArenas), 0, stream, used);
+        if (vec4) FLTOP_LAUNCH_PRUNE(true, false);
+        else FLTOP_LAUNCH_PRUNE(false, false);
+    }
+#undef FLTOP_LAUNCH_PRUNE
     return hipGetLastError();
 }
 

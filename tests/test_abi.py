@@ -65,8 +65,19 @@ def test_workspace_bytes(lib):
     big = binding.workspace_bytes(64, 500, 32, 32)
     assert 0 < small < big
     assert small % 256 == 0
-    # survivor records (8 B per token per frame) are the floor
-    assert big >= 64 * 500 * 32 * 8
+    # worst case: every frame keeps every token, six in its header, the others as 8-byte records;
+    # a budget gets some slack on top (the record array is handed out in 64 slices, and each may
+    # end on a stretch shorter than one wavefront's request: 8 frames x 26 records at V = 32)
+    fixed = binding.workspace_bytes(64, 500, 32, 32, max_records=0)
+    assert 0 < fixed < big and fixed % 256 == 0
+    slack = 64 * 8 * (32 - 6)
+    assert big - fixed == (64 * 500 * (32 - 6) + slack) * 8
+    # a record budget in between; more than the shapes can need changes nothing
+    mid = binding.workspace_bytes(64, 500, 32, 32, max_records=1000)
+    assert fixed + (1000 + slack) * 8 <= mid <= fixed + (1000 + slack + 64) * 8 + 256
+    assert binding.workspace_bytes(64, 500, 32, 32, max_records=10 ** 12) == big
+    # six tokens or fewer never need a record
+    assert binding.workspace_bytes(3, 50, 6, 4) == binding.workspace_bytes(3, 50, 6, 4, max_records=0)
 
 
 def test_argument_errors_are_reported_before_any_launch(lib):
@@ -76,6 +87,7 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     p.beam = 8
     p.rel_threshold = 0.01
     need = binding.workspace_bytes(2, 10, 32, 8)
+    least = binding.workspace_bytes(2, 10, 32, 8, max_records=0)  # smaller ones are refused
 
     def call(lp=fake, ln=fake, B=2, T=10, V=32, params=p, ws=fake, nbytes=need, tok=fake,
              olen=fake, sc=fake):
@@ -93,7 +105,7 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     assert call(T=0) == -2
     assert call(V=1) == -2
     assert call(V=binding.MAX_VOCAB + 1) == -6
-    assert call(nbytes=need - 1) == -5
+    assert call(nbytes=least - 1) == -5
     assert call(ws=ctypes.c_void_p(256 * 4096 + 8)) == -8
     for bad_beam in (0, -3, binding.MAX_BEAM + 1):
         q = binding.FltopParams()
@@ -134,7 +146,7 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     big = binding.FltopParams()
     big.beam = 100
     big.rel_threshold = 0.01
-    assert binding.workspace_bytes(256, 1500, 32, 100) > binding.STATIC_SCRATCH_BYTES
+    assert binding.workspace_bytes(256, 1500, 32, 100, max_records=0) > binding.STATIC_SCRATCH_BYTES
     assert lib.fltop_ctc_decode_static(fake, fake, 256, 1500, 32, ctypes.byref(big), fake, fake,
                                        fake, None, None) == -10
     assert lib.fltop_ctc_decode_static(fake, fake, 2, 10, 32, None, fake, fake, fake, None,
@@ -191,7 +203,7 @@ def test_stream_entry_points_validate_before_any_launch(lib):
     assert call(st=None) == -1
     assert call(Tchunk=0) == -2
     assert call(total=Tc - 1) == -2          # a chunk longer than the whole stream
-    assert call(ws_bytes=ws_need - 1) == -5
+    assert call(ws_bytes=binding.workspace_bytes(B, Tc, V, 8, max_records=0) - 1) == -5
     assert call(st_bytes=st_need - 1) == -5
     assert call(st=ctypes.c_void_p(256 * 4096 + 64)) == -8
     q = binding.FltopParams()

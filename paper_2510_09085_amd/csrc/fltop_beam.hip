@@ -1275,14 +1275,21 @@ void beam_kernel(BeamArgs a) {
                 const int cs = (int)hcoarse[lane];
                 const int incl = wave_inclusive_scan(cs);
                 const int total = __builtin_amdgcn_readlane(incl, kWave - 1);
+                // The two rows of fine bins looked at below -- the one with the first occupied
+                // bin (lanes 0..15) and the one in which the need-th candidate lies (lanes
+                // 16..31) -- are asked for together: one LDS round trip instead of two.
+                const uint64_t occ = __ballot(cs > 0);
+                const uint64_t cross = __ballot(incl >= need);
+                const int lmin = occ != 0 ? __ffsll((long long)occ) - 1 : 0;
+                const int lstar = cross != 0 ? __ffsll((long long)cross) - 1 : 0;
+                const int fine_row = (lane & 16) ? lstar : lmin;
+                const int fine_val = (int)hfine[fine_row * 16 + (lane & 15)];
                 if (iter == 0) {
                     pd_cand += (uint32_t)total;
                     pd_peak = max(pd_peak, (uint32_t)total);
                     // first occupied bin -> bound of the best candidate (window starts at 0)
-                    const uint64_t occ = __ballot(cs > 0);
                     if (occ != 0) {
-                        const int lmin = __ffsll((long long)occ) - 1;
-                        const uint32_t f = hfine[lmin * 16 + (lane & 15)];
+                        const uint32_t f = (uint32_t)fine_val;
                         const uint64_t occf = __ballot(f > 0 && lane < 16);
                         const int bmin = lmin * 16 + (__ffsll((long long)occf) - 1);
                         const uint64_t dmin = (w.sh > 0 && ((uint64_t)bmin >> (64 - w.sh)) != 0)
@@ -1297,18 +1304,18 @@ void beam_kernel(BeamArgs a) {
                     selH = kAllOnes;
                     break;
                 }
-                // coarse bin holding the need-th candidate, then the fine bin inside it
-                const uint64_t cross = __ballot(incl >= need);
-                const int lstar = __ffsll((long long)cross) - 1;
+                // coarse bin holding the need-th candidate (lstar), then the fine bin inside it
+                // (its row sits in lanes 16..31; the row scan works within each 16 lanes)
                 const int above_c =
                     __builtin_amdgcn_readlane(incl, lstar) - __builtin_amdgcn_readlane(cs, lstar);
-                const int fs = (int)hfine[lstar * 16 + (lane & 15)];
+                const int fs = fine_val;
                 const int fincl = row_inclusive_scan(fs);
-                const uint64_t fcross = __ballot(lane < 16 && above_c + fincl >= need);
+                const uint64_t fcross =
+                    __ballot((lane & 48) == 16 && above_c + fincl >= need) >> 16;
                 const int fl = __ffsll((long long)fcross) - 1;
                 const int bstar = lstar * 16 + fl;
-                const int n_b = __builtin_amdgcn_readlane(fs, fl);
-                const int n_above = above_c + __builtin_amdgcn_readlane(fincl, fl) - n_b;
+                const int n_b = __builtin_amdgcn_readlane(fs, 16 + fl);
+                const int n_above = above_c + __builtin_amdgcn_readlane(fincl, 16 + fl) - n_b;
                 const int r = need - n_above;  // 1 <= r <= n_b
                 const bool clamp_bin = (bstar == kFine - 1) && (w.sh < kMaxShift);
 

@@ -302,8 +302,11 @@ __device__ __forceinline__ double lse2(double a, double b) {
     return hi + log1p_unit(exp_nonpositive(lo - hi));
 }
 
+// number of set bits of `mask` below this lane's own position
 __device__ inline int lanes_below(uint64_t mask, int lane) {
-    return __popcll(mask & ((1ull << lane) - 1ull));
+    (void)lane;
+    return (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
+                                          __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
 }
 
 __device__ inline uint64_t sat_add(uint64_t a, uint64_t b) {
@@ -1418,20 +1421,23 @@ void beam_kernel(BeamArgs a) {
                 D_stay != kAllOnes && is_selected(fc, selD, selH, D_stay, tid, -1, hhs, hvs);
             const bool sel_0 =
                 cD0 != kAllOnes && is_selected(fc, selD, selH, cD0, cI0, cT0, hh0, hv0);
-            const int cnt = (sel_s ? 1 : 0) + (sel_0 ? 1 : 0);
-            const int incl = wave_inclusive_scan(cnt);
-            const int wave_total = __builtin_amdgcn_readlane(incl, kWave - 1);
+            // places inside the wavefront from two ballots (the selected stays first, then the
+            // selected extensions): a handful of scalar and count instructions
+            const uint64_t m_s = __ballot(sel_s), m_0 = __ballot(sel_0);
+            const int n_s = __popcll(m_s);
+            const int wave_total = n_s + __popcll(m_0);
             int base = 0;
             if (wave_total > 0) {
                 if (lane == 0) base = atomicAdd(&sh_nnew, wave_total);
                 base = __builtin_amdgcn_readfirstlane(base);
             }
-            int slot = base + incl - cnt;
+            const int slot_s = base + lanes_below(m_s, lane);
+            const int slot_0 = base + n_s + lanes_below(m_0, lane);
             PHASE_MARK(9);
             if (sel_s)
-                emit_stay(fc, nxt, lkn, ccur, cnxt, newslot, slot++, beam, tid, my_pb, my_pnb, my_tot);
+                emit_stay(fc, nxt, lkn, ccur, cnxt, newslot, slot_s, beam, tid, my_pb, my_pnb, my_tot);
             if (sel_0)
-                emit_ext(fc, nxt, lkn, ccur, cnxt, slot++, beam, t_base + t, cD0, cI0, cT0, hh0, hv0,
+                emit_ext(fc, nxt, lkn, ccur, cnxt, slot_0, beam, t_base + t, cD0, cI0, cT0, hh0, hv0,
                          trie, trie_stride);
         }
         for (int m = kRegCand; m < M; ++m) {  // candidates beyond the register cache

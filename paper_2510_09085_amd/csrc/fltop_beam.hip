@@ -1481,6 +1481,13 @@ void beam_kernel(BeamArgs a) {
             n_new = beam;
         }
         pd_beam += (uint32_t)n_new;
+        // A run of blank-only frames that follows inside this chunk is taken here: the thread
+        // that owns a place of the new beam adds the run's log-probs to its total, one by one in
+        // frame order, behind the barrier this frame ends on anyway.  (A run at the start of a
+        // chunk or of the utterance takes the path at the top of the loop.)
+        int run_after = 0;
+        if (l + 1 < kChunk && n_new > 0)
+            run_after = __builtin_ctz(~(blank_only >> (l + 1)) | 0x80000000u);
         if (tid < n_new) {
             int p = -1;
             const int32_t code = lkn->par[tid];
@@ -1544,7 +1551,22 @@ void beam_kernel(BeamArgs a) {
         }
         n_live = n_new;
         gen ^= 1;
-        collapsed = false;  // every entry of the new beam carries its own p_b / p_nb
+        collapsed = run_after > 0;  // otherwise every entry carries its own p_b / p_nb
+        if (run_after > 0) {
+            double own = tid < n_new ? nxt->ptot[tid] : 0.0;
+            for (int k = 0; k < run_after; ++k) {
+                const double x = (double)__int_as_float(__builtin_amdgcn_readlane(lp_bits, l + 1 + k));
+                own += x;
+                kmax_v += x;
+                kmin_v += x;
+            }
+            if (tid < n_new) nxt->ptot[tid] = own;
+            pd_cand += (uint32_t)(n_new * run_after);
+            pd_peak = max(pd_peak, (uint32_t)n_new);
+            pd_beam += (uint32_t)(n_new * run_after);
+            if (a.frame_beam && tid < run_after) a.frame_beam[trace_base + t + 1 + tid] = n_new;
+            t += run_after;
+        }
         lds_barrier();
         PHASE_MARK(6);
     }  // frames of the chunk

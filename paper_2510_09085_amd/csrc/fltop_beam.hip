@@ -738,26 +738,45 @@ __device__ __forceinline__ void publish_hash(Links<MB>* lkn, uint64_t hh, int sl
     }
 }
 
+// What an entry that stays in the beam carries over unchanged.  It is read together with the
+// entry's masses when the stay candidate is evaluated, so that the copy into the next beam
+// does not begin with a round trip to wherever these fields live.
+struct StayFields {
+    uint64_t h, hp;
+    int32_t par, last, node, plen, xanc;
+};
+
 // Entry `se` keeps its prefix: copy it into `slot` of the next beam with its new masses.
-template <int MB>
+template <int MB, bool PREFETCHED>
 __device__ __forceinline__ void emit_stay(const FrameCtx<MB>& f, BeamSlab<MB>* nxt, Links<MB>* lkn,
                                           const ColdRef<MB>& ccur, const ColdRef<MB>& cnxt,
                                           int32_t* newslot, int slot, int beam, int se, double pb,
-                                          double pnb, double tot) {
+                                          double pnb, double tot, const StayFields& sf) {
     if (slot >= beam) return;  // only after a hash collision
-    const BeamSlab<MB>* cur = f.cur;
-    const uint64_t hh = cur->h[se];
     // where this entry went, and where its parent was (or -2: the parent was not in the
     // beam, so it can only be in the new one as a fresh extension)
-    const int32_t par_old = f.lk->par[se];
-    newslot[se] = slot;
-    lkn->par[slot] = par_old >= 0 ? par_old : -2;
-    nxt->h[slot] = hh;
-    nxt->pb[slot] = pb;
-    nxt->pnb[slot] = pnb;
-    nxt->ptot[slot] = tot;
-    nxt->last[slot] = cur->last[se];
-    cnxt.set(slot, ccur.hp(se), ccur.node(se), ccur.plen(se), ccur.xanc(se));
+    if constexpr (PREFETCHED) {
+        newslot[se] = slot;
+        lkn->par[slot] = sf.par >= 0 ? sf.par : -2;
+        nxt->h[slot] = sf.h;
+        nxt->pb[slot] = pb;
+        nxt->pnb[slot] = pnb;
+        nxt->ptot[slot] = tot;
+        nxt->last[slot] = sf.last;
+        cnxt.set(slot, sf.hp, sf.node, sf.plen, sf.xanc);
+    } else {
+        const BeamSlab<MB>* cur = f.cur;
+        const uint64_t hh = cur->h[se];
+        const int32_t par_old = f.lk->par[se];
+        newslot[se] = slot;
+        lkn->par[slot] = par_old >= 0 ? par_old : -2;
+        nxt->h[slot] = hh;
+        nxt->pb[slot] = pb;
+        nxt->pnb[slot] = pnb;
+        nxt->ptot[slot] = tot;
+        nxt->last[slot] = cur->last[se];
+        cnxt.set(slot, ccur.hp(se), ccur.node(se), ccur.plen(se), ccur.xanc(se));
+    }
 }
 
 // Entry `se` extended by token `tk` becomes a new prefix in `slot`; its trie node id is
@@ -808,6 +827,10 @@ void beam_kernel(BeamArgs a) {
     // builds with 512 threads or more take a thread's candidates from one entry (see EntryView)
     constexpr bool kEntryMajor = THREADS >= kThreadsLarge;
     static_assert(kEntryMajor || !kColdGlobal, "the largest capacity has no children lists");
+    // Builds with four wavefronts read what a staying entry carries over together with its
+    // masses (measured: cfg 3 -1.7%); the larger builds, shorter of registers, read it when the
+    // entry is copied (measured there: +0.4% to +1.4% otherwise).
+    constexpr bool kPrefetchStay = !kEntryMajor;
     constexpr int kKidSlots = kEntryMajor ? (kColdGlobal ? 2 * MB : 4 * MB) : 4;
     __shared__ uint32_t kidset2[2][kKidSlots];  // (parent place, token) pairs, per generation
     __shared__ BeamSlab<MB> slab[2];
@@ -1178,14 +1201,26 @@ void beam_kernel(BeamArgs a) {
         // ... and the stay candidate of entry `tid`
         double my_pb = -INFINITY, my_pnb = -INFINITY, my_tot = -INFINITY;
         uint64_t D_stay = kAllOnes;
+        StayFields sf;
+        sf.h = sf.hp = 0;
+        sf.par = sf.last = sf.node = sf.plen = sf.xanc = -1;
         if (tid < n_live) {
             const int j = tid;
             const int32_t lj = cur->last[j];
+            if constexpr (kPrefetchStay) {
+                sf.h = cur->h[j];
+                sf.hp = ccur.hp(j);
+                sf.node = ccur.node(j);
+                sf.plen = ccur.plen(j);
+                sf.xanc = ccur.xanc(j);
+                sf.last = lj;
+            }
             const double lpl = lp_of(fc, lj);
             my_pb = cur->ptot[j] + lp_blank;
             const double a1 = (collapsed ? -INFINITY : cur->pnb[j]) + lpl;
             double a2 = -INFINITY;
             const int p = lk->par[j];
+            if constexpr (kPrefetchStay) sf.par = p;
             if (p >= 0 && lpl > -INFINITY) {
                 const int32_t lpar = cur->last[p];
                 const double ptp = cur->ptot[p];
@@ -1435,7 +1470,8 @@ void beam_kernel(BeamArgs a) {
             const int slot_0 = base + n_s + lanes_below(m_0, lane);
             PHASE_MARK(9);
             if (sel_s)
-                emit_stay(fc, nxt, lkn, ccur, cnxt, newslot, slot_s, beam, tid, my_pb, my_pnb, my_tot);
+                emit_stay<MB, kPrefetchStay>(fc, nxt, lkn, ccur, cnxt, newslot, slot_s, beam, tid, my_pb,
+                                             my_pnb, my_tot, sf);
             if (sel_0)
                 emit_ext(fc, nxt, lkn, ccur, cnxt, slot_0, beam, t_base + t, cD0, cI0, cT0, hh0, hv0,
                          trie, trie_stride);

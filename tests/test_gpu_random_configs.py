@@ -96,3 +96,33 @@ def test_random_configurations_with_beams_beyond_512(oracle_lib, seed0):
             beams=[100, 512, 513, 600, 1000, 1023, binding.MAX_BEAM])
         check_case(dev, oracle_lib, lp, ln, beam, r, top_n, window,
                    f"seed {seed0} case {case}: {label}", lm=lm, lm_weight=0.7, insertion_bonus=0.3)
+
+
+@pytest.mark.parametrize("seed0", [31, 32])
+def test_random_configurations_on_peaky_emissions(oracle_lib, seed0):
+    """Emissions of the workload generator (a dominant token per frame, so a threshold leaves
+    runs of blank-only frames of every length, also across the 32-frame header chunks of the
+    search kernel), with utterance lengths, beams of all three capacities, thresholds, top-N,
+    windows and bigram tables drawn at random.  Same bars as above."""
+    from test_gpu_ties import check_case
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    dev = torch.device("cuda:0")
+    rng = np.random.default_rng(seed0)
+    for case in range(50):
+        V = int(rng.choice([2, 3, 32, 32, 33, 100, 1024]))
+        beam = int(rng.choice([1, 8, 32, 64, 100, 128, 129, 513, 1000]))
+        r = float(rng.choice([1e-3, 0.007, 0.01, 0.01, 0.1, 0.5, 1.0]))
+        top_n = int(rng.choice([0, 0, 1, 4]))
+        window = float(rng.choice([0.0, 0.0, 3.0, 25.0]))
+        B = int(rng.choice([1, 3, 9]))
+        T = int(rng.integers(2, 400))
+        w = synth.Workload("random", B=B, T=T, V=V, beam=beam, rel_thresholds=(r,),
+                           seed=seed0 * 100000 + case,
+                           hard_rate=float(rng.choice([0.1, 0.25, 0.5])))
+        lp, _ = synth.make_emissions(w)
+        ln = rng.integers(0, T + 1, size=B).astype(np.int32)
+        ln[0] = T
+        lm = synth.make_bigram_lm(V, seed=case) if rng.random() < 0.3 else None
+        check_case(dev, oracle_lib, lp, ln, beam, r, top_n, window,
+                   f"seed {seed0} case {case}: B{B} T{T} V{V} beam{beam} r{r} N{top_n} "
+                   f"window{window} lm{lm is not None}", lm=lm, lm_weight=0.7, insertion_bonus=0.3)

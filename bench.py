@@ -631,8 +631,8 @@ PHASES = (  # (index in fltop_stats.phase_clocks, what the span covers), in pipe
     (9, "slot allocation in the next beam"),
     (5, "emit into the next beam, trie stores, barrier 2"),
     (10, "parent / children links of the new beam"),
-    (6, "housekeeping, barrier 3"),
-    (7, "runs of blank-only frames (per run)"),
+    (6, "housekeeping, a following run of blank-only frames, barrier 3"),
+    (7, "blank-only runs at the start of a 32-frame header chunk"),
 )
 
 
@@ -667,7 +667,7 @@ def phase_clock_table(args, torch, binding, synth, dev):
         if idx != 7:
             totals = [a + b for a, b in zip(totals, row)]
         print(f"{what:66s} " + " ".join(f"{x:8.0f}" for x in row))
-    print(f"{'sum without the blank-only runs':66s} " + " ".join(f"{x:8.0f}" for x in totals))
+    print(f"{'sum without the last row':66s} " + " ".join(f"{x:8.0f}" for x in totals))
 
 
 def counter_probe(args, torch, binding, synth, dev):

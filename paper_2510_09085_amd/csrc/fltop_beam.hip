@@ -831,6 +831,13 @@ void beam_kernel(BeamArgs a) {
     // masses (measured: cfg 3 -1.7%); the larger builds, shorter of registers, read it when the
     // entry is copied (measured there: +0.4% to +1.4% otherwise).
     constexpr bool kPrefetchStay = !kEntryMajor;
+    // Which way a uniform branch of the frame loop usually goes, for the block layout of the
+    // four-wavefront builds: a lone wavefront per SIMD pays for every taken branch, and with the
+    // usual path laid out straight a frame is 2-4% shorter (the set below was chosen by timing
+    // builds with each hint on and off; the builds with 512 and 1024 threads gained nothing from
+    // any of them and are left to the compiler's own guesses).
+#define FLTOP_RARE(c) (kEntryMajor ? !!(c) : __builtin_expect(!!(c), 0))
+#define FLTOP_USUAL(c) (kEntryMajor ? !!(c) : __builtin_expect(!!(c), 1))
     constexpr int kKidSlots = kEntryMajor ? (kColdGlobal ? 2 * MB : 4 * MB) : 4;
     __shared__ uint32_t kidset2[2][kKidSlots];  // (parent place, token) pairs, per generation
     __shared__ BeamSlab<MB> slab[2];
@@ -1044,13 +1051,13 @@ void beam_kernel(BeamArgs a) {
 
     for (int t = c * kChunk; t < t_end; ++t) {
         const int l = t & (kChunk - 1);
-        if (n_live == 0) {  // the beam died: nothing left to decode
+        if (FLTOP_RARE(n_live == 0)) {  // the beam died: nothing left to decode
             if (a.frame_beam && tid < t_end - t) a.frame_beam[trace_base + t + tid] = 0;
             break;
         }
         // ---- run of blank-only frames --------------------------------------------------
         const int run = __builtin_ctz(~(blank_only >> l) | 0x80000000u);
-        if (run > 0) {
+        if (FLTOP_RARE(run > 0)) {
             // every entry's total takes the run's log-probs one by one, in frame order, as a
             // plain implementation adds them (the owner thread keeps the sum in a register)
             BeamSlab<MB>* const cur_run = &slab[gen];
@@ -1107,7 +1114,7 @@ void beam_kernel(BeamArgs a) {
         }
         if (tid >= kThreads / 2 && tid - kThreads / 2 < kMaxBeam / 4)
             reinterpret_cast<int4*>(newslot)[tid - kThreads / 2] = make_int4(-1, -1, -1, -1);
-        if (big && hd.rec_base == kNoRecords) {  // uniform: the record array was too small
+        if (FLTOP_RARE(big && hd.rec_base == kNoRecords)) {  // uniform: the record array was too small
             failed = true;
             break;
         }
@@ -1253,7 +1260,7 @@ void beam_kernel(BeamArgs a) {
             int need = beam;
             const bool windowed = a.beam_window > 0.0;  // uniform
             for (int iter = 0; iter < 40; ++iter) {
-                if (iter > 0) {  // rare: the single histogram is reused for a refined window
+                if (FLTOP_RARE(iter > 0)) {  // rare: the single histogram is reused for a refined window
                     lds_barrier();
                     for (int i = tid; i < kFine; i += kThreads) hfine[i] = 0u;
                     if (tid < kCoarse) hcoarse[tid] = 0u;
@@ -1265,7 +1272,7 @@ void beam_kernel(BeamArgs a) {
                 if (windowed) {
                     nearest = D_stay < cD0 ? D_stay : cD0;
                 }
-                if (M > kRegCand) {
+                if (FLTOP_RARE(M > kRegCand)) {
                     int n_clamp = 0;
                     for (int m = kRegCand; m < M; ++m) {
                         int e, k;
@@ -1326,7 +1333,7 @@ void beam_kernel(BeamArgs a) {
                     pd_cand += (uint32_t)total;
                     pd_peak = max(pd_peak, (uint32_t)total);
                     // first occupied bin -> bound of the best candidate (window starts at 0)
-                    if (occ != 0) {
+                    if (FLTOP_USUAL(occ != 0)) {
                         const uint32_t f = (uint32_t)fine_val;
                         const uint64_t occf = __ballot(f > 0 && lane < 16);
                         const int bmin = lmin * 16 + (__ffsll((long long)occf) - 1);
@@ -1337,7 +1344,7 @@ void beam_kernel(BeamArgs a) {
                     }
                 }
                 ++pd_pass;
-                if (total <= need) {  // everything left in the window is kept
+                if (FLTOP_RARE(total <= need)) {  // everything left in the window is kept
                     selD = (w.mode == 0) ? kAllOnes : w.Dfix;
                     selH = kAllOnes;
                     break;
@@ -1357,7 +1364,7 @@ void beam_kernel(BeamArgs a) {
                 const int r = need - n_above;  // 1 <= r <= n_b
                 const bool clamp_bin = (bstar == kFine - 1) && (w.sh < kMaxShift);
 
-                if (n_b == r) {  // the boundary bucket is taken whole
+                if (FLTOP_USUAL(n_b == r)) {  // the boundary bucket is taken whole
                     const uint64_t top = clamp_bin ? kAllOnes : bucket_top(w.lo, bstar, w.sh);
                     if (w.mode == 0) {
                         selD = top;
@@ -1368,7 +1375,7 @@ void beam_kernel(BeamArgs a) {
                     }
                     break;
                 }
-                if (n_b <= kExactCap) {
+                if (FLTOP_USUAL(n_b <= kExactCap)) {
                     // ---- exact ranking of the boundary bucket by (distance, hash)
                     ++pd_exact;
                     if (D_stay != kAllOnes)
@@ -1441,7 +1448,7 @@ void beam_kernel(BeamArgs a) {
                 }
             }
         }
-        if (Dcut < selD) {  // the score window is narrower than the top-`beam` cut
+        if (FLTOP_RARE(Dcut < selD)) {  // the score window is narrower than the top-`beam` cut
             selD = Dcut;
             selH = kAllOnes;
         }
@@ -1512,7 +1519,7 @@ void beam_kernel(BeamArgs a) {
 
         // ---- adopt the new beam; rebuild parent / children links ---------------------
         int n_new = __builtin_amdgcn_readfirstlane(sh_nnew);  // the same in every lane
-        if (n_new > beam) {
+        if (FLTOP_RARE(n_new > beam)) {
             pd_drop += (uint32_t)(n_new - beam);
             n_new = beam;
         }
@@ -1607,6 +1614,8 @@ void beam_kernel(BeamArgs a) {
         PHASE_MARK(6);
     }  // frames of the chunk
     }  // chunks
+#undef FLTOP_RARE
+#undef FLTOP_USUAL
 #undef FLTOP_LOAD_CHUNK
 #undef FLTOP_RING_HEAD
 

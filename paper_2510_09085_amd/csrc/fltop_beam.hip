@@ -42,6 +42,8 @@
 // candidate mapping where frames hold hundreds to thousands of candidates, and two with a
 // tighter register budget for batches that fill the chip, where instruction issue and
 // residency count instead of one frame's latency (see launch_beam).
+#include <type_traits>
+
 #include "fltop_internal.h"
 
 namespace fltop {
@@ -1259,8 +1261,18 @@ void beam_kernel(BeamArgs a) {
             w.Dfix = 0;
             int need = beam;
             const bool windowed = a.beam_window > 0.0;  // uniform
-            for (int iter = 0; iter < 40; ++iter) {
-                if (FLTOP_RARE(iter > 0)) {  // rare: the single histogram is reused for a refined window
+            // One pass over the candidates: histogram, scan, and either the threshold (true) or a
+            // narrower window for the next pass (false).  The first pass, the only one in all but
+            // a few frames, is compiled with its window constants folded in.
+            auto pass = [&](auto first_tag) -> bool {
+                constexpr bool kFirst = decltype(first_tag)::value;
+                if (kFirst) {
+                    w.lo = 0;
+                    w.mode = 0;
+                    w.Dfix = 0;
+                    need = beam;
+                }
+                if (!kFirst) {  // rare: the single histogram is reused for a refined window
                     lds_barrier();
                     for (int i = tid; i < kFine; i += kThreads) hfine[i] = 0u;
                     if (tid < kCoarse) hcoarse[tid] = 0u;
@@ -1281,7 +1293,7 @@ void beam_kernel(BeamArgs a) {
                         int32_t tk = 0;
                         uint64_t D;
                         const int row = m - kRegCand;
-                        if (iter > 0 && row < drows) {
+                        if (!kFirst && row < drows) {
                             D = dcache[row * kThreads];
                             if (w.mode != 0 && D == w.Dfix) cand_name(e, k, se, tk);  // for its hash
                         } else {
@@ -1298,7 +1310,7 @@ void beam_kernel(BeamArgs a) {
                         atomicAdd(&hcoarse[kCoarse - 1], (uint32_t)wave_clamp);
                     }
                 }
-                if (windowed && iter == 0) {  // one LDS atomic per wavefront
+                if (kFirst && windowed) {  // one LDS atomic per wavefront
                     const uint64_t wave_nearest = wave_min_u64(nearest);
                     if (lane == 0 && wave_nearest != kAllOnes)
                         atomicMin((unsigned long long*)&sh_minD,
@@ -1306,7 +1318,7 @@ void beam_kernel(BeamArgs a) {
                 }
                 lds_barrier();
                 PHASE_MARK(2);
-                if (windowed && iter == 0) {
+                if (kFirst && windowed) {
                     // the frame's best score, exactly; the window's floor in the same fp64
                     // subtraction a plain implementation does, mapped back to a distance
                     const uint64_t minD = sh_minD;
@@ -1329,7 +1341,7 @@ void beam_kernel(BeamArgs a) {
                 const int lstar = cross != 0 ? __ffsll((long long)cross) - 1 : 0;
                 const int fine_row = (lane & 16) ? lstar : lmin;
                 const int fine_val = (int)hfine[fine_row * 16 + (lane & 15)];
-                if (iter == 0) {
+                if (kFirst) {
                     pd_cand += (uint32_t)total;
                     pd_peak = max(pd_peak, (uint32_t)total);
                     // first occupied bin -> bound of the best candidate (window starts at 0)
@@ -1347,7 +1359,7 @@ void beam_kernel(BeamArgs a) {
                 if (FLTOP_RARE(total <= need)) {  // everything left in the window is kept
                     selD = (w.mode == 0) ? kAllOnes : w.Dfix;
                     selH = kAllOnes;
-                    break;
+                    return true;
                 }
                 // coarse bin holding the need-th candidate (lstar), then the fine bin inside it
                 // (its row sits in lanes 16..31; the row scan works within each 16 lanes)
@@ -1373,7 +1385,7 @@ void beam_kernel(BeamArgs a) {
                         selD = w.Dfix;
                         selH = top;
                     }
-                    break;
+                    return true;
                 }
                 if (FLTOP_USUAL(n_b <= kExactCap)) {
                     // ---- exact ranking of the boundary bucket by (distance, hash)
@@ -1424,7 +1436,7 @@ void beam_kernel(BeamArgs a) {
                     selD = sh_selD;
                     selH = sh_selH;
                     PHASE_MARK(4);
-                    break;
+                    return true;
                 }
                 // ---- boundary bucket too large: narrow (or widen) the window
                 need = r;
@@ -1444,9 +1456,12 @@ void beam_kernel(BeamArgs a) {
                     // identical score and identical hash (collision): keep them all
                     selD = w.Dfix;
                     selH = w.lo + (uint64_t)bstar;
-                    break;
+                    return true;
                 }
-            }
+                return false;
+            };
+            bool found = pass(std::true_type{});
+            for (int iter = 1; !found && iter < 40; ++iter) found = pass(std::false_type{});
         }
         if (FLTOP_RARE(Dcut < selD)) {  // the score window is narrower than the top-`beam` cut
             selD = Dcut;

@@ -1281,7 +1281,7 @@ void beam_kernel(BeamArgs a) {
                 if (D_stay != kAllOnes) hist_add(fc, w, D_stay, tid, -1, hfine, hcoarse);
                 if (cD0 != kAllOnes) hist_add(fc, w, cD0, cI0, cT0, hfine, hcoarse);
                 uint64_t nearest = kAllOnes;  // this thread's best candidate (score window only)
-                if (windowed) {
+                if (FLTOP_RARE(windowed)) {
                     nearest = D_stay < cD0 ? D_stay : cD0;
                 }
                 if (FLTOP_RARE(M > kRegCand)) {

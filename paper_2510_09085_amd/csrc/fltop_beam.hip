@@ -734,9 +734,10 @@ template <int MB>
 __device__ __forceinline__ void publish_hash(Links<MB>* lkn, uint64_t hh, int slot) {
     constexpr int kHashSlots = SlabTraits<MB>::kHashSlots;
     uint32_t hs = (uint32_t)hh & (kHashSlots - 1);
-    for (int probe = 0; probe < kHashSlots; ++probe) {
-        if (atomicCAS(&lkn->ht[hs], -1, slot) == -1) break;
+    if (atomicCAS(&lkn->ht[hs], -1, slot) == -1) return;  // the usual case: the first place is free
+    for (int probe = 1; probe < kHashSlots; ++probe) {
         hs = (hs + 1) & (kHashSlots - 1);
+        if (atomicCAS(&lkn->ht[hs], -1, slot) == -1) break;
     }
 }
 
@@ -1554,14 +1555,17 @@ void beam_kernel(BeamArgs a) {
             } else if (cnxt.plen(tid) > 0) {
                 const uint64_t want = cnxt.hp(tid);
                 uint32_t hs = (uint32_t)want & (kHashSlots - 1);
-                for (int probe = 0; probe < kHashSlots; ++probe) {
-                    const int v = lkn->ht[hs];
-                    if (v < 0) break;
-                    if (nxt->h[v] == want) {
-                        p = v;
-                        break;
+                int v = lkn->ht[hs];
+                if (v >= 0) {  // rare: something hashes to this place; walk on until found or free
+                    for (int probe = 0; probe < kHashSlots; ++probe) {
+                        if (nxt->h[v] == want) {
+                            p = v;
+                            break;
+                        }
+                        hs = (hs + 1) & (kHashSlots - 1);
+                        v = lkn->ht[hs];
+                        if (v < 0) break;
                     }
-                    hs = (hs + 1) & (kHashSlots - 1);
                 }
             }
             lkn->par[tid] = p;

@@ -1056,7 +1056,8 @@ void beam_kernel(BeamArgs a) {
         const int l = t & (kChunk - 1);
         if (FLTOP_RARE(n_live == 0)) {  // the beam died: nothing left to decode
             if (a.frame_beam && tid < t_end - t) a.frame_beam[trace_base + t + tid] = 0;
-            break;
+            t = t_end;  // (the loop keeps its single exit: leaving it from several places costs
+            continue;   // every frame a dispatch on the way round)
         }
         // ---- run of blank-only frames --------------------------------------------------
         const int run = __builtin_ctz(~(blank_only >> l) | 0x80000000u);
@@ -1119,7 +1120,8 @@ void beam_kernel(BeamArgs a) {
             reinterpret_cast<int4*>(newslot)[tid - kThreads / 2] = make_int4(-1, -1, -1, -1);
         if (FLTOP_RARE(big && hd.rec_base == kNoRecords)) {  // uniform: the record array was too small
             failed = true;
-            break;
+            t = t_end;
+            continue;
         }
         if (big) {
             const Survivor* recs = rec_all + ((int64_t)hd.rec_base - kRegK);

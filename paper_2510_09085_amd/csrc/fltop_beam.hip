@@ -1464,7 +1464,7 @@ void beam_kernel(BeamArgs a) {
                 return false;
             };
             bool found = pass(std::true_type{});
-            for (int iter = 1; !found && iter < 40; ++iter) found = pass(std::false_type{});
+            for (int iter = 1; FLTOP_RARE(!found && iter < 40); ++iter) found = pass(std::false_type{});
         }
         if (FLTOP_RARE(Dcut < selD)) {  // the score window is narrower than the top-`beam` cut
             selD = Dcut;

@@ -1291,7 +1291,7 @@ void beam_kernel(BeamArgs a) {
                     int n_clamp = 0;
                     for (int m = kRegCand; m < M; ++m) {
                         int e, k;
-                        if (!cand_at(m, e, k)) break;
+                        if (!cand_at(m, e, k)) continue;  // (and none at any later m)
                         int se = 0;
                         int32_t tk = 0;
                         uint64_t D;
@@ -1399,7 +1399,7 @@ void beam_kernel(BeamArgs a) {
                         boundary_add(fc, w, bstar, cD0, cI0, cT0, &sh_blcount, bl_D, bl_h);
                     for (int m = kRegCand; m < M; ++m) {
                         int e, k;
-                        if (!cand_at(m, e, k)) break;
+                        if (!cand_at(m, e, k)) continue;  // (and none at any later m)
                         int se = 0;
                         int32_t tk = 0;
                         uint64_t D;

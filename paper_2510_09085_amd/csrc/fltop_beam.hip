@@ -601,13 +601,14 @@ __device__ __forceinline__ void kidset_insert(uint32_t* kidset, int slots, int p
 __device__ __forceinline__ bool kidset_has(const uint32_t* kidset, int slots, int parent, int32_t tok) {
     const uint32_t key = kid_key(parent, tok);
     uint32_t hs = (key * 2654435761u >> 12) & (slots - 1);
-    for (int probe = 0; probe < slots; ++probe) {
+    bool found = false, done = false;  // (one way out of the loop)
+    for (int probe = 0; probe < slots && !done; ++probe) {
         const uint32_t v = kidset[hs];
-        if (v == key) return true;
-        if (v == kNoKid) return false;
+        found = v == key;
+        done = found || v == kNoKid;
         hs = (hs + 1) & (slots - 1);
     }
-    return false;
+    return found;
 }
 
 // (token, log-prob) of survivor k, the staged ones by rank

@@ -1588,17 +1588,23 @@ void beam_kernel(BeamArgs a) {
             // 16 bytes per store
             const int u = tid - kThreads / 2;
             const int4 ones = make_int4(-1, -1, -1, -1), zeros = make_int4(0, 0, 0, 0);
-            for (int i = u; i < kHashSlots / 4; i += kThreads / 2)
-                reinterpret_cast<int4*>(lk->ht)[i] = ones;
+            // (trip counts known at compile time: straight-line stores, no loops)
+            constexpr int kHalf = kThreads / 2;
+            auto fill = [&](int4* dst, auto n_tag, const int4& v) {
+                constexpr int n = decltype(n_tag)::value;  // 16-byte words to fill
+#pragma unroll
+                for (int j = 0; j < n / kHalf; ++j) dst[u + j * kHalf] = v;
+                if (n % kHalf != 0 && u < n % kHalf) dst[u + (n / kHalf) * kHalf] = v;
+            };
+            fill(reinterpret_cast<int4*>(lk->ht), std::integral_constant<int, kHashSlots / 4>{}, ones);
             if (kEntryMajor)
-                for (int i = u; i < kKidSlots / 4; i += kThreads / 2)
-                    reinterpret_cast<int4*>(kidset2[gen])[i] = ones;
-            for (int i = u; i < kMaxBeam / 4; i += kThreads / 2) {
-                if (!kColdGlobal) reinterpret_cast<int4*>(lk->first_kid)[i] = ones;
-                reinterpret_cast<int4*>(lk->kidmask)[i] = zeros;
-            }
-            for (int i = u; i < kFine / 4; i += kThreads / 2)
-                reinterpret_cast<int4*>(hfine)[i] = zeros;
+                fill(reinterpret_cast<int4*>(kidset2[gen]), std::integral_constant<int, kKidSlots / 4>{},
+                     ones);
+            if (!kColdGlobal)
+                fill(reinterpret_cast<int4*>(lk->first_kid), std::integral_constant<int, kMaxBeam / 4>{},
+                     ones);
+            fill(reinterpret_cast<int4*>(lk->kidmask), std::integral_constant<int, kMaxBeam / 4>{}, zeros);
+            fill(reinterpret_cast<int4*>(hfine), std::integral_constant<int, kFine / 4>{}, zeros);
             if (u < kCoarse / 4) reinterpret_cast<int4*>(hcoarse)[u] = zeros;
         }
         if (tid == 0) {

@@ -1552,14 +1552,21 @@ void beam_kernel(BeamArgs a) {
             run_after = __builtin_ctz(~(blank_only >> (l + 1)) | 0x80000000u);
         if (tid < n_new) {
             int p = -1;
-            const int32_t code = lkn->par[tid];
-            if (code >= 0) {
-                p = newslot[code];  // the parent was in the old beam: did it stay, and where
-            } else if (cnxt.plen(tid) > 0) {
+            if constexpr (!kColdGlobal) {
+                // Two LDS round trips: everything the entry's own fields can say, asked for
+                // together; then ONE lookup, in the table of moves if the parent was in the old
+                // beam (did it stay, and where), else in the hash table of the new prefixes
+                // (a parent that was not in the beam can only have entered it just now).
+                const int32_t code = lkn->par[tid];
+                const int32_t depth = cnxt.plen(tid);
                 const uint64_t want = cnxt.hp(tid);
+                const int32_t tok_me = nxt->last[tid];
                 uint32_t hs = (uint32_t)want & (kHashSlots - 1);
-                int v = lkn->ht[hs];
-                if (v >= 0) {  // rare: something hashes to this place; walk on until found or free
+                const int32_t* where = code >= 0 ? &newslot[code] : &lkn->ht[hs];
+                int v = *where;
+                if (code >= 0) {
+                    p = v;
+                } else if (depth > 0 && v >= 0) {  // rare: walk on until found or free
                     for (int probe = 0; probe < kHashSlots; ++probe) {
                         if (nxt->h[v] == want) {
                             p = v;
@@ -1570,14 +1577,42 @@ void beam_kernel(BeamArgs a) {
                         if (v < 0) break;
                     }
                 }
-            }
-            lkn->par[tid] = p;
-            if (p >= 0) {
-                if (kEntryMajor)
-                    kidset_insert(kidset2[gen ^ 1], kKidSlots, p, nxt->last[tid]);
-                else
-                    lkn->next_kid[tid] = atomicExch(&lkn->first_kid[p], tid);
-                atomicOr(&lkn->kidmask[p], 1u << (nxt->last[tid] & 31));
+                lkn->par[tid] = p;
+                if (p >= 0) {
+                    if (kEntryMajor)
+                        kidset_insert(kidset2[gen ^ 1], kKidSlots, p, tok_me);
+                    else
+                        lkn->next_kid[tid] = atomicExch(&lkn->first_kid[p], tid);
+                    atomicOr(&lkn->kidmask[p], 1u << (tok_me & 31));
+                }
+            } else {
+                const int32_t code = lkn->par[tid];
+                if (code >= 0) {
+                    p = newslot[code];  // the parent was in the old beam: did it stay, and where
+                } else if (cnxt.plen(tid) > 0) {
+                    const uint64_t want = cnxt.hp(tid);
+                    uint32_t hs = (uint32_t)want & (kHashSlots - 1);
+                    int v = lkn->ht[hs];
+                    if (v >= 0) {  // rare: something hashes to this place; walk on until found or free
+                        for (int probe = 0; probe < kHashSlots; ++probe) {
+                            if (nxt->h[v] == want) {
+                                p = v;
+                                break;
+                            }
+                            hs = (hs + 1) & (kHashSlots - 1);
+                            v = lkn->ht[hs];
+                            if (v < 0) break;
+                        }
+                    }
+                }
+                lkn->par[tid] = p;
+                if (p >= 0) {
+                    if (kEntryMajor)
+                        kidset_insert(kidset2[gen ^ 1], kKidSlots, p, nxt->last[tid]);
+                    else
+                        lkn->next_kid[tid] = atomicExch(&lkn->first_kid[p], tid);
+                    atomicOr(&lkn->kidmask[p], 1u << (nxt->last[tid] & 31));
+                }
             }
         }
         PHASE_MARK(10);

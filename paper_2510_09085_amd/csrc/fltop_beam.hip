@@ -1550,6 +1550,7 @@ void beam_kernel(BeamArgs a) {
         int run_after = 0;
         if (l + 1 < kChunk && n_new > 0)
             run_after = __builtin_ctz(~(blank_only >> (l + 1)) | 0x80000000u);
+        double own_total = 0.0;  // of the entry this thread owns in the new beam (for the run)
         if (tid < n_new) {
             int p = -1;
             if constexpr (!kColdGlobal) {
@@ -1561,6 +1562,7 @@ void beam_kernel(BeamArgs a) {
                 const int32_t depth = cnxt.plen(tid);
                 const uint64_t want = cnxt.hp(tid);
                 const int32_t tok_me = nxt->last[tid];
+                own_total = nxt->ptot[tid];
                 uint32_t hs = (uint32_t)want & (kHashSlots - 1);
                 const int32_t* where = code >= 0 ? &newslot[code] : &lkn->ht[hs];
                 int v = *where;
@@ -1659,7 +1661,8 @@ void beam_kernel(BeamArgs a) {
         gen ^= 1;
         collapsed = run_after > 0;  // otherwise every entry carries its own p_b / p_nb
         if (run_after > 0) {
-            double own = tid < n_new ? nxt->ptot[tid] : 0.0;
+            double own = own_total;
+            if (kColdGlobal && tid < n_new) own = nxt->ptot[tid];
             for (int k = 0; k < run_after; ++k) {
                 const double x = (double)__int_as_float(__builtin_amdgcn_readlane(lp_bits, l + 1 + k));
                 own += x;

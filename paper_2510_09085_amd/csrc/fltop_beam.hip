@@ -532,9 +532,18 @@ __device__ __forceinline__ void cand_of(const FrameCtx<MB>& f, int e, int& entry
     tok = surv_tok_lp(f, f.nb0 + k, lp);
 }
 
-template <int LM, int MB>
+// What a new prefix takes over from the entry it extends.  Builds with four wavefronts read it
+// together with that entry's masses when the thread's first extension is evaluated, so that
+// entering the beam does not begin with a round trip to LDS.
+struct ExtSource {
+    uint64_t h;  // the entry's prefix hash
+    int32_t node, plen, xanc;
+};
+
+template <int LM, int MB, bool WITH_SOURCE = false>
 __device__ __forceinline__ uint64_t eval_ext(const FrameCtx<MB>& f, int e, int& src_entry,
-                                             int32_t& tok) {
+                                             int32_t& tok, const ColdRef<MB>* cold = nullptr,
+                                             ExtSource* source = nullptr) {
     int i;
     int32_t s;
     double lps;
@@ -546,6 +555,12 @@ __device__ __forceinline__ uint64_t eval_ext(const FrameCtx<MB>& f, int e, int& 
     const uint32_t km = f.lk->kidmask[i];
     const double pti = f.cur->ptot[i];
     const double pbi = f.collapsed ? pti : f.cur->pb[i];
+    if constexpr (WITH_SOURCE) {
+        source->h = f.cur->h[i];
+        source->node = cold->node(i);
+        source->plen = cold->plen(i);
+        source->xanc = cold->xanc(i);
+    }
     if ((km >> (s & 31)) & 1u) {  // maybe a child i+s is in the beam
         int guard = 0;
         for (int kid = f.lk->first_kid[i]; kid >= 0 && guard < MB;
@@ -806,6 +821,40 @@ __device__ __forceinline__ void emit_ext(const FrameCtx<MB>& f, BeamSlab<MB>* nx
     cnxt.set(slot, cur->h[se], node, depth, (depth & 7) == 0 ? node : xa);
     TrieNode tn;
     tn.parent = ccur.node(se);
+    tn.xup = xa;
+    tn.tok = tk;
+    tn.depth = depth;
+    if ((int64_t)node < trie_stride) trie[node] = tn;
+    lkn->par[slot] = se;  // the parent's place in the old beam
+    publish_hash(lkn, hh, slot);
+}
+
+// The same with what the new prefix takes over from entry `se` already in registers.
+template <int MB>
+__device__ __forceinline__ void emit_ext_prefetched(const FrameCtx<MB>& f, BeamSlab<MB>* nxt, Links<MB>* lkn,
+                                         const ColdRef<MB>& ccur, const ColdRef<MB>& cnxt, int slot,
+                                         int beam, int t, uint64_t D, int se, int32_t tk,
+                                         uint64_t hh, bool have_h, TrieNode* trie,
+                                         int64_t trie_stride, const ExtSource* source) {
+    constexpr bool WITH_SOURCE = true;
+    if (slot >= beam) return;
+    const BeamSlab<MB>* cur = f.cur;
+    if (!have_h) {
+        if constexpr (WITH_SOURCE) hh = child_hash(source->h, tk);
+        else hh = cand_hash(f, se, tk);
+    }
+    const double sc = key_value(f.Rk - D);
+    const int node = 1 + t * beam + slot;
+    const int depth = (WITH_SOURCE ? source->plen : ccur.plen(se)) + 1;
+    const int32_t xa = WITH_SOURCE ? source->xanc : ccur.xanc(se);
+    nxt->h[slot] = hh;
+    nxt->pb[slot] = -INFINITY;
+    nxt->pnb[slot] = sc;
+    nxt->ptot[slot] = sc;
+    nxt->last[slot] = tk;
+    cnxt.set(slot, WITH_SOURCE ? source->h : cur->h[se], node, depth, (depth & 7) == 0 ? node : xa);
+    TrieNode tn;
+    tn.parent = WITH_SOURCE ? source->node : ccur.node(se);
     tn.xup = xa;
     tn.tok = tk;
     tn.depth = depth;
@@ -1199,16 +1248,18 @@ void beam_kernel(BeamArgs a) {
         // ---- candidates owned by this thread ----------------------------------------
         // the first extension candidate stays in registers (the others, if any, are worked
         // on one after the other and leave their distances in LDS) ...
+        ExtSource xs0{};
         uint64_t cD0 = kAllOnes;  // ~0 marks "no live candidate"
         int cI0 = 0;
         int32_t cT0 = 0;
-        if (kEntryMajor) {
+        if constexpr (kEntryMajor) {
             if (ext_thread) {
                 ev = view_entry(fc, ext_i);
                 cD0 = cand_eval(0, ext_g, cI0, cT0);
             }
         } else {
-            if (e_first < n_ext) cD0 = eval_ext<LM>(fc, e_first, cI0, cT0);
+            if (e_first < n_ext)
+                cD0 = eval_ext<LM, MB, kPrefetchStay>(fc, e_first, cI0, cT0, &ccur, &xs0);
         }
         PHASE_MARK(8);
         // ... and the stay candidate of entry `tid`
@@ -1499,8 +1550,14 @@ void beam_kernel(BeamArgs a) {
                 emit_stay<MB, kPrefetchStay>(fc, nxt, lkn, ccur, cnxt, newslot, slot_s, beam, tid, my_pb,
                                              my_pnb, my_tot, sf);
             if (sel_0)
-                emit_ext(fc, nxt, lkn, ccur, cnxt, slot_0, beam, t_base + t, cD0, cI0, cT0, hh0, hv0,
-                         trie, trie_stride);
+            {
+                if constexpr (kPrefetchStay)
+                    emit_ext_prefetched(fc, nxt, lkn, ccur, cnxt, slot_0, beam, t_base + t, cD0, cI0,
+                                        cT0, hh0, hv0, trie, trie_stride, &xs0);
+                else
+                    emit_ext(fc, nxt, lkn, ccur, cnxt, slot_0, beam, t_base + t, cD0, cI0, cT0, hh0,
+                             hv0, trie, trie_stride);
+            }
         }
         for (int m = kRegCand; m < M; ++m) {  // candidates beyond the register cache
             int e, k;

